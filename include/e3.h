@@ -1,0 +1,168 @@
+/*
+ * libe3 -- the per-token vocabulary pass, group advantages and temperature
+ * scheduler of "E3" (arXiv 2505.18573) for AMD MI355X (gfx950).
+ *
+ * C ABI: plain pointers and sizes only.  Unless a parameter says "host", every
+ * pointer is DEVICE memory on the current HIP device.  The caller owns all
+ * buffers; the library never retains a pointer.  Device entry points only
+ * enqueue work on `hip_stream` (a hipStream_t passed as void*, NULL = the
+ * default stream) and return without synchronising: outputs are valid once the
+ * stream has reached that point.  All argument checks happen on the host before
+ * anything is launched; on error nothing is launched and outputs are untouched.
+ * Results are bit-reproducible for fixed inputs (no floating-point atomics).
+ *
+ * Return value: 0 (E3_OK) or a negative e3_status.
+ */
+#ifndef E3_H
+#define E3_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    E3_OK = 0,
+    E3_ERR_NULL = -1,      /* a required pointer is NULL */
+    E3_ERR_SHAPE = -2,     /* rows < 0, V < 1, row_stride < V, num_groups < 0 ... */
+    E3_ERR_DTYPE = -3,     /* dtype is not an e3_dtype */
+    E3_ERR_ALIGN = -4,     /* logits base or row pitch not 16-byte aligned */
+    E3_ERR_VALUE = -5,     /* a scalar is outside its domain (tau <= 0, H <= 0, ...) */
+    E3_ERR_WORKSPACE = -6, /* workspace missing or smaller than e3_workspace_bytes() */
+    E3_ERR_LAUNCH = -7     /* the HIP runtime refused a launch (see hipGetLastError) */
+} e3_status;
+
+typedef enum { E3_F32 = 0, E3_BF16 = 1 } e3_dtype;
+
+/*
+ * Column partition of the two-level sampler (see e3_sample_entropy).  Columns
+ * are cut into chunks of E3_TILE_CHUNK; chunks are dealt round-robin to
+ * E3_TILE_LANES slots; a tile is E3_TILE_DEPTH successive chunks of one slot:
+ *   tile(i) = (i / (CHUNK*LANES*DEPTH)) * LANES + (i % (CHUNK*LANES)) / CHUNK.
+ * These constants are part of the definition of the sampled token.
+ */
+#define E3_TILE_CHUNK 8
+#define E3_TILE_LANES 64
+#define E3_TILE_DEPTH 16
+
+/* Static, never-freed description of a status code (host). */
+const char* e3_strerror(int status);
+
+/*
+ * Bytes of device workspace that e3_sample_entropy / e3_logprob_entropy need
+ * for a [rows, V] problem (pure host function; 0 means none is needed and
+ * `workspace` may then be NULL).  The workspace holds per-row partial results
+ * when rows are few enough that one row is split over several workgroups.
+ */
+size_t e3_workspace_bytes(int64_t rows, int64_t V);
+
+/*
+ * Rollout side: sample one token per row at temperature tau_r and report its
+ * log-probability and the entropy of the tau-scaled distribution.
+ *
+ *   a_i = z_i / tau_r,  p_i = exp(a_i) / sum_j exp(a_j)      (Appendix A, softmax)
+ *   H   = -sum_i p_i ln p_i                                   (Appendix A, entropy;
+ *         evaluated as ln S - W/S, the appendix's decomposition
+ *         H = beta sum p_i Delta_i + ln Z(beta) in max-shifted form)
+ *   tok ~ p by two-level Gumbel-max (the paper samples "at temperature tau",
+ *         Section 5.1, without describing a sampler; this is the library's):
+ *         tile T* = argmax_T ( ln sum_{i in T} exp(a_i) + g_T ),
+ *         tok     = argmax_{i in T*} ( a_i + g_i ),  g = -ln(-ln u),
+ *         u = ((w >> 9) + 1/2) 2^-23, w = word (index % 4) of
+ *         Philox4x32-10( counter = (index/4, row lo, row hi, stream),
+ *                        key = (seed lo, seed hi) ),
+ *         stream 1 / index = tile id for g_T, stream 2 / index = column for g_i,
+ *         row = row_base + r.  Exact ties go to the lowest index.  By
+ *         max-stability of the Gumbel law P(tok = i) = p_i exactly.
+ *   logp = a_tok - ln sum_j exp(a_j)
+ *
+ * logits      [rows, row_stride] elements of `dtype`, row-major, first V of each
+ *             row used; base 16-byte aligned and row_stride*sizeof(elem) a
+ *             multiple of 16 (else E3_ERR_ALIGN).  Values must be finite; a row
+ *             holding NaN or +-inf produces NaN outputs and an unspecified token
+ *             in [0, V).
+ * tau_rows    [rows] fp32 or NULL; when NULL tau_scalar (host, finite, > 0, else
+ *             E3_ERR_VALUE) applies to every row.  Per-row values are not checked:
+ *             a row with tau <= 0 produces NaN outputs.
+ * seed, row_base  host scalars; row_base is the global id of row 0, so results do
+ *             not depend on how rows are batched.
+ * token_out   [rows] int32;  logp_out, entropy_out [rows] fp32 (natural log).
+ *             logp_out and entropy_out may be NULL.
+ * workspace   device scratch of at least e3_workspace_bytes(rows, V) bytes,
+ *             256-byte aligned; contents need not be initialised.
+ * rows == 0 is a no-op.  fp32 accumulation per lane, fp64 merges.
+ */
+int e3_sample_entropy(const void* logits, int dtype, int64_t rows, int64_t V, int64_t row_stride,
+                      const float* tau_rows, float tau_scalar,
+                      uint64_t seed, uint64_t row_base,
+                      int32_t* token_out, float* logp_out, float* entropy_out,
+                      void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
+ * Training side: log-probability of a given token and the entropy of each row,
+ * with the logits divided by the temperature as in the policy forward pass (end
+ * of the "Temperature Scheduler" paragraph of Section 4.2), plus the two numbers
+ * from which the batch-mean entropy H_t of Eq. 4 follows.
+ *
+ * target_ids  [rows] int32 or NULL; an id outside [0, V) gives logp = NaN.
+ *             NULL requires logp_out == NULL.
+ * row_mask    [rows] uint8 or NULL; rows with mask 0 (padding) are still written
+ *             to logp_out/entropy_out but excluded from the batch sum.
+ * logp_out    [rows] fp32 or NULL;  entropy_out [rows] fp32 (required).
+ * entropy_sum_out    one double (device) or NULL: sum of entropy_out over kept
+ *             rows, accumulated in fp64 in a fixed order.
+ * entropy_count_out  one int64 (device) or NULL: number of kept rows.
+ * Other arguments as for e3_sample_entropy.
+ */
+int e3_logprob_entropy(const void* logits, int dtype, int64_t rows, int64_t V, int64_t row_stride,
+                       const int32_t* target_ids, const uint8_t* row_mask,
+                       const float* tau_rows, float tau_scalar,
+                       float* logp_out, float* entropy_out,
+                       double* entropy_sum_out, int64_t* entropy_count_out,
+                       void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
+ * Group-relative advantage, Eq. 2:  A_i = (r_i - mean(r)) / std(r) over the
+ * rollouts of one prompt, groups stored CSR-style because Algorithm 1 gives each
+ * prompt its own rollout budget.
+ *
+ * rewards        [N] fp32, N = group_offsets[num_groups].
+ * group_offsets  [num_groups + 1] int32, non-decreasing, group_offsets[0] = 0
+ *                (caller's contract; not checked on the device).  Empty groups
+ *                write nothing.
+ * ddof           0 = population standard deviation (the literal formula),
+ *                1 = Bessel-corrected.
+ * eps            >= 0, added to the standard deviation.
+ * adv_out        [N] fp32.  A group whose rewards are all identical (exact
+ *                compare; includes groups of one) gets 0 for every rollout
+ *                (Section 4.2: identical rewards give zero advantage).
+ * Sums are taken in fp64.  num_groups == 0 is a no-op.
+ */
+int e3_grpo_advantages(const float* rewards, const int32_t* group_offsets,
+                       int32_t num_groups, int32_t ddof, float eps,
+                       float* adv_out, void* hip_stream);
+
+/*
+ * Temperature scheduler, host only (no GPU work, all pointers are HOST):
+ *   H_target = H_init                                      for t < t_anneal or t_anneal < 0
+ *            = H_init [eta + (1-eta)(1 + cos(pi x))/2]      otherwise (Eq. 5),
+ *              x = clamp((t - t_anneal)/(t_max - t_anneal), 0, 1), x = 1 if t_max <= t_anneal
+ *   alpha    = H_target / H_t
+ *   tau_next = tau_t (1 + tau_t ln(alpha) / (ln|V| + ln ln|V|))               (Eq. 4)
+ * then clamped to [tau_min, tau_max]; (0, +inf) leaves Eq. 4 untouched.
+ * E3_ERR_VALUE if tau_t, H_t, H_init are not finite and > 0, vocab < 3, eta
+ * outside [0,1], tau_min < 0, tau_max < tau_min, or the factor is <= 0 while
+ * tau_min == 0.  On error the outputs are untouched.
+ * tau_next_out required; H_target_out may be NULL.
+ */
+int e3_temperature_update(double tau_t, double H_t, double H_init, int64_t vocab,
+                          int64_t t, int64_t t_anneal, int64_t t_max, double eta,
+                          double tau_min, double tau_max,
+                          double* tau_next_out, double* H_target_out);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* E3_H */

@@ -1,0 +1,11 @@
+"""MI355X-native hot path of E3 (arXiv 2505.18573): fused temperature-softmax entropy,
+token log-prob and Gumbel-max sampling over [rows, V] logits, GRPO group advantages over
+CSR groups, and the closed-form temperature scheduler.  The arithmetic lives in libe3.so
+(HIP, gfx950); this package is its ctypes binding plus seeded workload generators."""
+from .binding import (E3_BF16, E3_F32, E3Error, e3_grpo_advantages, e3_logprob_entropy,
+                      e3_sample_entropy, e3_strerror, e3_temperature_update,
+                      e3_workspace_bytes, lib)
+
+__all__ = ["E3_BF16", "E3_F32", "E3Error", "e3_grpo_advantages", "e3_logprob_entropy",
+           "e3_sample_entropy", "e3_strerror", "e3_temperature_update", "e3_workspace_bytes",
+           "lib"]

@@ -1,0 +1,208 @@
+"""Python binding of libe3.so: argument marshalling only.
+
+Every function has the name and the arguments of the C entry point it calls
+(include/e3.h).  Tensors are torch tensors used as device memory; the current
+torch stream is handed over as the hipStream_t.  Nothing is computed here, and
+there is no fallback: without the built library the import of `lib()` raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional, Tuple
+
+import torch
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "libe3.so")
+
+E3_F32, E3_BF16 = 0, 1
+E3_OK = 0
+E3_TILE_CHUNK, E3_TILE_LANES, E3_TILE_DEPTH = 8, 64, 16
+
+EXPORTS = ("e3_strerror", "e3_workspace_bytes", "e3_sample_entropy", "e3_logprob_entropy",
+           "e3_grpo_advantages", "e3_temperature_update")
+
+_lib: Optional[C.CDLL] = None
+
+
+class E3Error(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {e3_strerror(status)} (status {status})")
+
+
+def lib() -> C.CDLL:
+    """Load libe3.so (built in-tree by paper_2505_18573_amd/build.py)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise ImportError(f"{LIB_PATH} is missing: run `python -m paper_2505_18573_amd.build` "
+                              "(there is no fallback path)")
+        L = C.CDLL(LIB_PATH)
+        vp, i32, i64, u64, f32, f64 = C.c_void_p, C.c_int32, C.c_int64, C.c_uint64, C.c_float, C.c_double
+        L.e3_strerror.argtypes = [C.c_int]
+        L.e3_strerror.restype = C.c_char_p
+        L.e3_workspace_bytes.argtypes = [i64, i64]
+        L.e3_workspace_bytes.restype = C.c_size_t
+        L.e3_sample_entropy.argtypes = [vp, C.c_int, i64, i64, i64, vp, f32, u64, u64,
+                                        vp, vp, vp, vp, C.c_size_t, vp]
+        L.e3_sample_entropy.restype = C.c_int
+        L.e3_logprob_entropy.argtypes = [vp, C.c_int, i64, i64, i64, vp, vp, vp, f32,
+                                         vp, vp, vp, vp, vp, C.c_size_t, vp]
+        L.e3_logprob_entropy.restype = C.c_int
+        L.e3_grpo_advantages.argtypes = [vp, vp, i32, i32, f32, vp, vp]
+        L.e3_grpo_advantages.restype = C.c_int
+        L.e3_temperature_update.argtypes = [f64, f64, f64, i64, i64, i64, i64, f64, f64, f64, vp, vp]
+        L.e3_temperature_update.restype = C.c_int
+        _lib = L
+    return _lib
+
+
+def _ptr(t: Optional[torch.Tensor]):
+    return None if t is None else C.c_void_p(t.data_ptr())
+
+
+def _stream(device) -> C.c_void_p:
+    return C.c_void_p(torch.cuda.current_stream(device).cuda_stream)
+
+
+def _logits_meta(logits: torch.Tensor) -> Tuple[int, int, int, int]:
+    if logits.dim() != 2 or (logits.shape[1] > 1 and logits.stride(1) != 1):
+        raise ValueError("logits must be [rows, V] with unit column stride")
+    if not logits.is_cuda:
+        raise ValueError("logits must live on the GPU")
+    if logits.dtype == torch.bfloat16:
+        dt = E3_BF16
+    elif logits.dtype == torch.float32:
+        dt = E3_F32
+    else:
+        raise TypeError(f"unsupported logit dtype {logits.dtype}")
+    rows, V = logits.shape
+    stride = logits.stride(0) if rows > 1 else max(V, logits.stride(0))
+    return dt, rows, V, stride
+
+
+def _check(t: Optional[torch.Tensor], dtype, n: int, name: str, device):
+    if t is None:
+        return
+    if t.dtype != dtype or t.dim() != 1 or t.shape[0] != n or not t.is_contiguous() \
+            or t.device != device:
+        raise ValueError(f"{name} must be a contiguous {dtype} tensor of {n} elements on {device}")
+
+
+def e3_strerror(status: int) -> str:
+    return lib().e3_strerror(int(status)).decode()
+
+
+def e3_workspace_bytes(rows: int, V: int) -> int:
+    return int(lib().e3_workspace_bytes(rows, V))
+
+
+def _workspace(rows: int, V: int, workspace: Optional[torch.Tensor], device):
+    need = e3_workspace_bytes(rows, V)
+    if need == 0:
+        return None, 0
+    if workspace is None:
+        workspace = torch.empty(need, dtype=torch.uint8, device=device)
+    return workspace, workspace.numel() * workspace.element_size()
+
+
+def e3_sample_entropy(logits: torch.Tensor, tau_rows: Optional[torch.Tensor], tau_scalar: float,
+                      seed: int, row_base: int = 0,
+                      token_out: Optional[torch.Tensor] = None,
+                      logp_out: Optional[torch.Tensor] = None,
+                      entropy_out: Optional[torch.Tensor] = None,
+                      workspace: Optional[torch.Tensor] = None):
+    """Returns (token int32 [rows], logp fp32 [rows], entropy fp32 [rows])."""
+    dt, rows, V, stride = _logits_meta(logits)
+    dev = logits.device
+    if token_out is None:
+        token_out = torch.empty(rows, dtype=torch.int32, device=dev)
+    if logp_out is None:
+        logp_out = torch.empty(rows, dtype=torch.float32, device=dev)
+    if entropy_out is None:
+        entropy_out = torch.empty(rows, dtype=torch.float32, device=dev)
+    _check(tau_rows, torch.float32, rows, "tau_rows", dev)
+    _check(token_out, torch.int32, rows, "token_out", dev)
+    _check(logp_out, torch.float32, rows, "logp_out", dev)
+    _check(entropy_out, torch.float32, rows, "entropy_out", dev)
+    ws, ws_bytes = _workspace(rows, V, workspace, dev)
+    rc = lib().e3_sample_entropy(_ptr(logits), dt, rows, V, stride, _ptr(tau_rows),
+                                 float(tau_scalar), int(seed), int(row_base),
+                                 _ptr(token_out), _ptr(logp_out), _ptr(entropy_out),
+                                 _ptr(ws), ws_bytes, _stream(dev))
+    if rc != E3_OK:
+        raise E3Error(rc, "e3_sample_entropy")
+    return token_out, logp_out, entropy_out
+
+
+def e3_logprob_entropy(logits: torch.Tensor, target_ids: Optional[torch.Tensor],
+                       row_mask: Optional[torch.Tensor], tau_rows: Optional[torch.Tensor],
+                       tau_scalar: float,
+                       logp_out: Optional[torch.Tensor] = None,
+                       entropy_out: Optional[torch.Tensor] = None,
+                       entropy_sum_out: Optional[torch.Tensor] = None,
+                       entropy_count_out: Optional[torch.Tensor] = None,
+                       workspace: Optional[torch.Tensor] = None, want_sum: bool = True):
+    """Returns (logp fp32 [rows] or None, entropy fp32 [rows], entropy_sum fp64 [1] or None,
+    entropy_count int64 [1] or None); the sum and count stay on the device."""
+    dt, rows, V, stride = _logits_meta(logits)
+    dev = logits.device
+    if logp_out is None and target_ids is not None:
+        logp_out = torch.empty(rows, dtype=torch.float32, device=dev)
+    if entropy_out is None:
+        entropy_out = torch.empty(rows, dtype=torch.float32, device=dev)
+    if want_sum and entropy_sum_out is None:
+        entropy_sum_out = torch.empty(1, dtype=torch.float64, device=dev)
+    if want_sum and entropy_count_out is None:
+        entropy_count_out = torch.empty(1, dtype=torch.int64, device=dev)
+    _check(target_ids, torch.int32, rows, "target_ids", dev)
+    _check(row_mask, torch.uint8, rows, "row_mask", dev)
+    _check(tau_rows, torch.float32, rows, "tau_rows", dev)
+    _check(logp_out, torch.float32, rows, "logp_out", dev)
+    _check(entropy_out, torch.float32, rows, "entropy_out", dev)
+    _check(entropy_sum_out, torch.float64, 1, "entropy_sum_out", dev)
+    _check(entropy_count_out, torch.int64, 1, "entropy_count_out", dev)
+    ws, ws_bytes = _workspace(rows, V, workspace, dev)
+    rc = lib().e3_logprob_entropy(_ptr(logits), dt, rows, V, stride, _ptr(target_ids),
+                                  _ptr(row_mask), _ptr(tau_rows), float(tau_scalar),
+                                  _ptr(logp_out), _ptr(entropy_out),
+                                  _ptr(entropy_sum_out), _ptr(entropy_count_out),
+                                  _ptr(ws), ws_bytes, _stream(dev))
+    if rc != E3_OK:
+        raise E3Error(rc, "e3_logprob_entropy")
+    return logp_out, entropy_out, entropy_sum_out, entropy_count_out
+
+
+def e3_grpo_advantages(rewards: torch.Tensor, group_offsets: torch.Tensor, ddof: int = 0,
+                       eps: float = 0.0, adv_out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """Returns adv fp32 [N].  group_offsets is int32 [B+1] on the same device."""
+    dev = rewards.device
+    if not rewards.is_cuda:
+        raise ValueError("rewards must live on the GPU")
+    n = rewards.shape[0]
+    num_groups = group_offsets.shape[0] - 1
+    _check(rewards, torch.float32, n, "rewards", dev)
+    _check(group_offsets, torch.int32, num_groups + 1, "group_offsets", dev)
+    if adv_out is None:
+        adv_out = torch.empty(n, dtype=torch.float32, device=dev)
+    _check(adv_out, torch.float32, n, "adv_out", dev)
+    rc = lib().e3_grpo_advantages(_ptr(rewards), _ptr(group_offsets), num_groups, int(ddof),
+                                  float(eps), _ptr(adv_out), _stream(dev))
+    if rc != E3_OK:
+        raise E3Error(rc, "e3_grpo_advantages")
+    return adv_out
+
+
+def e3_temperature_update(tau_t: float, H_t: float, H_init: float, vocab: int, t: int = 0,
+                          t_anneal: int = -1, t_max: int = 0, eta: float = 1.0,
+                          tau_min: float = 0.0, tau_max: float = float("inf")):
+    """Host-only scheduler step.  Returns (tau_next, H_target)."""
+    nxt, tgt = C.c_double(float("nan")), C.c_double(float("nan"))
+    rc = lib().e3_temperature_update(float(tau_t), float(H_t), float(H_init), int(vocab), int(t),
+                                     int(t_anneal), int(t_max), float(eta), float(tau_min),
+                                     float(tau_max), C.addressof(nxt), C.addressof(tgt))
+    if rc != E3_OK:
+        raise E3Error(rc, "e3_temperature_update")
+    return nxt.value, tgt.value

@@ -1,0 +1,126 @@
+// C ABI of libe3: argument checks on the host, then kernel launches.
+#include <hip/hip_runtime.h>
+#include <cmath>
+#include <cstdint>
+
+#include "../../include/e3.h"
+#include "vocab_pass.h"
+
+namespace {
+
+int check_logits(const void* logits, int dtype, int64_t rows, int64_t V, int64_t row_stride)
+{
+    if (dtype != E3_F32 && dtype != E3_BF16) return E3_ERR_DTYPE;
+    if (rows < 0 || V < 1 || row_stride < V) return E3_ERR_SHAPE;
+    if (V > (int64_t)0x7FFFFFFF - 8192 || rows > (int64_t)0x7FFFFFFF) return E3_ERR_SHAPE;
+    if (rows == 0) return E3_OK;
+    if (logits == nullptr) return E3_ERR_NULL;
+    const int64_t esz = dtype == E3_F32 ? 4 : 2;
+    if ((reinterpret_cast<uintptr_t>(logits) & 15u) != 0 || ((row_stride * esz) & 15) != 0)
+        return E3_ERR_ALIGN;
+    return E3_OK;
+}
+
+int check_tau(const float* tau_rows, float tau_scalar)
+{
+    if (tau_rows != nullptr) return E3_OK;
+    return (std::isfinite(tau_scalar) && tau_scalar > 0.0f) ? E3_OK : E3_ERR_VALUE;
+}
+
+}  // namespace
+
+extern "C" const char* e3_strerror(int status)
+{
+    switch (status) {
+        case E3_OK: return "ok";
+        case E3_ERR_NULL: return "a required pointer is NULL";
+        case E3_ERR_SHAPE: return "bad shape (rows < 0, V < 1, row_stride < V, or too large)";
+        case E3_ERR_DTYPE: return "unknown dtype";
+        case E3_ERR_ALIGN: return "logits base or row pitch is not 16-byte aligned";
+        case E3_ERR_VALUE: return "scalar argument outside its domain";
+        case E3_ERR_WORKSPACE: return "workspace missing or too small";
+        case E3_ERR_LAUNCH: return "HIP launch failed";
+        default: return "unknown status";
+    }
+}
+
+extern "C" size_t e3_workspace_bytes(int64_t rows, int64_t V)
+{
+    (void)rows; (void)V;
+    return 0;   // every row is handled by one workgroup: nothing to stage
+}
+
+extern "C" int e3_sample_entropy(const void* logits, int dtype, int64_t rows, int64_t V,
+                                 int64_t row_stride, const float* tau_rows, float tau_scalar,
+                                 uint64_t seed, uint64_t row_base,
+                                 int32_t* token_out, float* logp_out, float* entropy_out,
+                                 void* workspace, size_t workspace_bytes, void* hip_stream)
+{
+    int rc = check_logits(logits, dtype, rows, V, row_stride);
+    if (rc != E3_OK) return rc;
+    rc = check_tau(tau_rows, tau_scalar);
+    if (rc != E3_OK) return rc;
+    if (rows == 0) return E3_OK;
+    if (token_out == nullptr) return E3_ERR_NULL;
+    const size_t need = e3_workspace_bytes(rows, V);
+    if (need > 0 && (workspace == nullptr || workspace_bytes < need)) return E3_ERR_WORKSPACE;
+
+    e3::VocabPassArgs a{};
+    a.logits = logits; a.rows = rows; a.V = V; a.row_stride = row_stride;
+    a.tau_rows = tau_rows; a.tau_scalar = tau_scalar;
+    a.seed = seed; a.row_base = row_base;
+    a.target_ids = nullptr;
+    a.token_out = token_out; a.logp_out = logp_out; a.entropy_out = entropy_out;
+    hipError_t err = e3::launch_vocab_pass(a, dtype == E3_BF16, true,
+                                           static_cast<hipStream_t>(hip_stream));
+    return err == hipSuccess ? E3_OK : E3_ERR_LAUNCH;
+}
+
+extern "C" int e3_logprob_entropy(const void* logits, int dtype, int64_t rows, int64_t V,
+                                  int64_t row_stride, const int32_t* target_ids,
+                                  const uint8_t* row_mask, const float* tau_rows, float tau_scalar,
+                                  float* logp_out, float* entropy_out,
+                                  double* entropy_sum_out, int64_t* entropy_count_out,
+                                  void* workspace, size_t workspace_bytes, void* hip_stream)
+{
+    int rc = check_logits(logits, dtype, rows, V, row_stride);
+    if (rc != E3_OK) return rc;
+    rc = check_tau(tau_rows, tau_scalar);
+    if (rc != E3_OK) return rc;
+    if (rows > 0 && entropy_out == nullptr) return E3_ERR_NULL;
+    if (logp_out != nullptr && target_ids == nullptr) return E3_ERR_NULL;
+    const size_t need = e3_workspace_bytes(rows, V);
+    if (need > 0 && (workspace == nullptr || workspace_bytes < need)) return E3_ERR_WORKSPACE;
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+
+    if (rows > 0) {
+        e3::VocabPassArgs a{};
+        a.logits = logits; a.rows = rows; a.V = V; a.row_stride = row_stride;
+        a.tau_rows = tau_rows; a.tau_scalar = tau_scalar;
+        a.target_ids = target_ids;
+        a.token_out = nullptr; a.logp_out = logp_out; a.entropy_out = entropy_out;
+        if (e3::launch_vocab_pass(a, dtype == E3_BF16, false, stream) != hipSuccess)
+            return E3_ERR_LAUNCH;
+    }
+    if (entropy_sum_out != nullptr || entropy_count_out != nullptr) {
+        // also for rows == 0: the sum and the count are then written as 0
+        if (e3::launch_entropy_reduce(entropy_out, row_mask, rows, entropy_sum_out,
+                                      entropy_count_out, stream) != hipSuccess)
+            return E3_ERR_LAUNCH;
+    }
+    return E3_OK;
+}
+
+extern "C" int e3_grpo_advantages(const float* rewards, const int32_t* group_offsets,
+                                  int32_t num_groups, int32_t ddof, float eps,
+                                  float* adv_out, void* hip_stream)
+{
+    if (num_groups < 0) return E3_ERR_SHAPE;
+    if (ddof != 0 && ddof != 1) return E3_ERR_VALUE;
+    if (!(eps >= 0.0f) || !std::isfinite(eps)) return E3_ERR_VALUE;
+    if (num_groups == 0) return E3_OK;
+    if (rewards == nullptr || group_offsets == nullptr || adv_out == nullptr) return E3_ERR_NULL;
+    hipError_t err = e3::launch_grpo_advantages(rewards, group_offsets, num_groups, ddof, eps,
+                                                adv_out, static_cast<hipStream_t>(hip_stream));
+    return err == hipSuccess ? E3_OK : E3_ERR_LAUNCH;
+}

@@ -1,0 +1,28 @@
+// Internal launch interface between the C ABI (e3_api.hip) and the kernels.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace e3 {
+
+struct VocabPassArgs {
+    const void* logits;
+    int64_t rows, V, row_stride;      // row_stride in elements
+    const float* tau_rows;            // device [rows] or nullptr
+    float tau_scalar;
+    uint64_t seed, row_base;          // sampling only
+    const int32_t* target_ids;        // training side, device [rows] or nullptr
+    int32_t* token_out;               // sampling only
+    float* logp_out;                  // nullable
+    float* entropy_out;               // nullable
+};
+
+hipError_t launch_vocab_pass(const VocabPassArgs& a, bool is_bf16, bool sample, hipStream_t stream);
+
+hipError_t launch_entropy_reduce(const float* entropy, const uint8_t* mask, int64_t rows,
+                                 double* sum_out, int64_t* count_out, hipStream_t stream);
+
+hipError_t launch_grpo_advantages(const float* rewards, const int32_t* offsets, int32_t num_groups,
+                                  int32_t ddof, float eps, float* adv_out, hipStream_t stream);
+
+}  // namespace e3

@@ -1,0 +1,525 @@
+// Vocabulary pass for gfx950: one coalesced HBM read of a [rows, V] logit matrix
+// that yields, per row, the entropy of softmax(z / tau), the log-probability of a
+// sampled or given token and (rollout side) a two-level Gumbel-max sample.
+//
+// Paper: arXiv 2505.18573.  Softmax with temperature and the Shannon entropy are
+// Appendix A's; the entropy is evaluated through the appendix's decomposition
+// H = beta * sum_i p_i Delta_i + ln Z(beta), which in running-reference form is
+// H = ln S - W/S with S = sum exp(a_i - ref), W = sum (a_i - ref) exp(a_i - ref).
+// The paper samples rollouts "at temperature tau" (Section 5.1) without describing
+// a sampler; the two-level Gumbel-max used here is specified in include/e3.h.
+//
+// Work decomposition (wave = 64 lanes):
+//   * a row is cut into super-tiles of 8192 columns; one wave streams a whole
+//     super-tile as 16 sweeps of 64 lanes x 8 columns (16 bytes of bf16 per lane),
+//     so every load instruction of a wave covers 1 KiB of contiguous memory;
+//   * the 16 chunks one lane sees inside a super-tile are exactly one sampler tile,
+//     so per-tile sums never leave the lane's registers;
+//   * each wave keeps one integer-valued log2 reference `rc` shared by its lanes
+//     (SGPR); it only moves when a sweep holds a new maximum, and moving it rescales
+//     by an exact power of two;
+//   * lanes accumulate in fp32, lane->wave->row merges run in fp64;
+//   * waves of a workgroup take super-tiles round-robin and meet once in LDS.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <type_traits>
+
+#include "vocab_pass.h"
+
+namespace e3 {
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int kChunk = 8;                       // columns per lane per sweep
+constexpr int kLanes = 64;                      // lanes = tiles per super-tile
+constexpr int kDepth = 16;                      // sweeps per super-tile
+constexpr int kSweepCols = kChunk * kLanes;     // 512
+constexpr int kSuperCols = kSweepCols * kDepth; // 8192
+constexpr double kLog2e = 1.4426950408889634074;
+constexpr double kLn2 = 0.69314718055994530942;
+
+// ---------------------------------------------------------------------------
+// wave-level helpers
+// ---------------------------------------------------------------------------
+__device__ __forceinline__ float wave_max(float v)
+{
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) v = fmaxf(v, __shfl_xor(v, off, 64));
+    return v;
+}
+
+__device__ __forceinline__ double wave_sum(double v)
+{
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
+    return v;
+}
+
+__device__ __forceinline__ float uniform_f(float v)
+{
+    return __uint_as_float(__builtin_amdgcn_readfirstlane(__float_as_uint(v)));
+}
+
+// Three-input maximum as one VALU instruction.  Written as asm because the
+// compiler would first canonicalise every operand that came out of integer
+// unpacking (one extra instruction per logit).
+__device__ __forceinline__ float fmax3(float a, float b, float c)
+{
+    float r;
+    asm("v_max3_f32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
+    return r;
+}
+
+// Candidate of a Gumbel-max race: larger weight wins, equal weights go to the
+// lower index.
+struct Cand { float q; int idx; };
+
+__device__ __forceinline__ Cand better(Cand a, Cand b)
+{
+    bool take_b = (b.q > a.q) || (b.q == a.q && b.idx < a.idx);
+    return take_b ? b : a;
+}
+
+__device__ __forceinline__ Cand wave_best(Cand c)
+{
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) {
+        Cand o;
+        o.q = __shfl_xor(c.q, off, 64);
+        o.idx = __shfl_xor(c.idx, off, 64);
+        c = better(c, o);
+    }
+    return c;
+}
+
+// ---------------------------------------------------------------------------
+// Philox4x32-10 (Salmon et al., SC'11) and the exponential variate -ln(u).
+// ---------------------------------------------------------------------------
+__device__ __forceinline__ void philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3,
+                                              uint32_t k0, uint32_t k1, uint32_t out[4])
+{
+    constexpr uint32_t MA = 0xD2511F53u, MB = 0xCD9E8D57u;
+#pragma unroll
+    for (int r = 0; r < 10; ++r) {
+        uint32_t ha = __umulhi(MA, c0), la = MA * c0;
+        uint32_t hb = __umulhi(MB, c2), lb = MB * c2;
+        uint32_t n0 = hb ^ c1 ^ k0;
+        uint32_t n2 = ha ^ c3 ^ k1;
+        c0 = n0; c1 = lb; c2 = n2; c3 = la;
+        k0 += 0x9E3779B9u; k1 += 0xBB67AE85u;
+    }
+    out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
+}
+
+// E = -ln(u), u = ((word >> 9) + 1/2) 2^-23.  u and d = 1 - u are exact in fp32.
+// Close to u = 1 the logarithm is taken from the series -ln(1-d) = sum d^k / k,
+// which keeps full relative accuracy where log(u) itself would cancel.
+__device__ __forceinline__ float exp_variate(uint32_t word)
+{
+    float k = (float)(word >> 9);
+    float u = fmaf(k, 0x1p-23f, 0x1p-24f);
+    float d = 1.0f - u;
+    float series = d * fmaf(d, fmaf(d, fmaf(d, fmaf(d, fmaf(d, fmaf(d, 1.0f / 7.0f, 1.0f / 6.0f),
+                   0.2f), 0.25f), 1.0f / 3.0f), 0.5f), 1.0f);
+    float direct = -logf(u);
+    return d < 0.0625f ? series : direct;
+}
+
+// ---------------------------------------------------------------------------
+// chunk loaders: 8 consecutive columns of one lane as fp32
+// ---------------------------------------------------------------------------
+struct ChunkBf16 {
+    u32x4 v;
+    static constexpr int kElemBytes = 2;
+    static constexpr int kAhead = 16;      // sweeps kept in flight per wave (16 KiB)
+    __device__ __forceinline__ void load(const char* row, int64_t col)
+    {
+        v = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(row + col * 2));
+    }
+    __device__ __forceinline__ void unpack(float z[8]) const
+    {
+        z[0] = __uint_as_float(v.x << 16); z[1] = __uint_as_float(v.x & 0xFFFF0000u);
+        z[2] = __uint_as_float(v.y << 16); z[3] = __uint_as_float(v.y & 0xFFFF0000u);
+        z[4] = __uint_as_float(v.z << 16); z[5] = __uint_as_float(v.z & 0xFFFF0000u);
+        z[6] = __uint_as_float(v.w << 16); z[7] = __uint_as_float(v.w & 0xFFFF0000u);
+    }
+    static __device__ __forceinline__ float load_one(const char* row, int64_t col)
+    {
+        return __uint_as_float((uint32_t)reinterpret_cast<const uint16_t*>(row)[col] << 16);
+    }
+};
+
+struct ChunkF32 {
+    u32x4 a, b;
+    static constexpr int kElemBytes = 4;
+    static constexpr int kAhead = 8;       // sweeps kept in flight per wave (16 KiB)
+    __device__ __forceinline__ void load(const char* row, int64_t col)
+    {
+        const u32x4* p = reinterpret_cast<const u32x4*>(row + col * 4);
+        a = __builtin_nontemporal_load(p);
+        b = __builtin_nontemporal_load(p + 1);
+    }
+    __device__ __forceinline__ void unpack(float z[8]) const
+    {
+        z[0] = __uint_as_float(a.x); z[1] = __uint_as_float(a.y);
+        z[2] = __uint_as_float(a.z); z[3] = __uint_as_float(a.w);
+        z[4] = __uint_as_float(b.x); z[5] = __uint_as_float(b.y);
+        z[6] = __uint_as_float(b.z); z[7] = __uint_as_float(b.w);
+    }
+    static __device__ __forceinline__ float load_one(const char* row, int64_t col)
+    {
+        return reinterpret_cast<const float*>(row)[col];
+    }
+};
+
+// ---------------------------------------------------------------------------
+// Per-lane running state of one wave.  rc is wave-uniform.
+// All sums are in base-2 units relative to rc:  t = z*c - rc,  e = 2^t.
+// ---------------------------------------------------------------------------
+struct LaneState {
+    float rc;          // shared reference, integer valued, -inf before the first element
+    float S, W;        // finished tiles:   sum e,  sum t*e
+    float sT0, sT1;    // current tile (two chains for instruction-level parallelism)
+    float wT0, wT1;
+    Cand best;         // best tile so far: q = tile mass / E_tile, idx = tile id
+};
+
+// Move the wave's reference up to cover a new maximum.  d is a non-negative
+// integer, so 2^-d is exact and the move costs no accuracy.
+__device__ __forceinline__ void raise_reference(LaneState& s, float chunk_max, float c)
+{
+    const float top = wave_max(chunk_max);
+    float new_rc = ceilf(top * c);
+    if (fmaf(top, c, -new_rc) > 0.0f) new_rc += 1.0f;   // product rounded down onto an integer
+    new_rc = uniform_f(new_rc);
+    if (s.rc > -INFINITY) {
+        float d = new_rc - s.rc;
+        float f = exp2f(-d);
+        s.W = fmaf(-d, s.S, s.W) * f;     s.S *= f;
+        s.wT0 = fmaf(-d, s.sT0, s.wT0) * f; s.sT0 *= f;
+        s.wT1 = fmaf(-d, s.sT1, s.wT1) * f; s.sT1 *= f;
+        s.best.q *= f;
+    }
+    s.rc = new_rc;
+}
+
+// Accumulate one chunk.  `valid` has bit j set when element j exists; the fast
+// path passes the constant 0xFF and the masking folds away.
+template <bool kAllValid>
+__device__ __forceinline__ void accumulate_chunk(LaneState& s, float z[8], unsigned valid, float c)
+{
+    if (!kAllValid) {
+#pragma unroll
+        for (int j = 0; j < 8; ++j)
+            if (!((valid >> j) & 1u)) z[j] = -INFINITY;
+    }
+    float cm = fmax3(fmax3(z[0], z[1], z[2]), fmax3(z[3], z[4], z[5]), fmax3(z[6], z[7], z[7]));
+    // t_max > 0 means the reference no longer covers this sweep (also true while rc = -inf)
+    float tmax = fmaf(cm, c, -s.rc);
+    if (__any(tmax > 0.0f)) raise_reference(s, cm, c);
+    const float nrc = -s.rc;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+        float zj = z[j];
+        if (!kAllValid) zj = ((valid >> j) & 1u) ? zj : 0.0f;
+        float t = fmaf(zj, c, nrc);
+        float e = __builtin_amdgcn_exp2f(t);
+        if (!kAllValid) e = ((valid >> j) & 1u) ? e : 0.0f;
+        if (j & 1) { s.sT1 += e; s.wT1 = fmaf(t, e, s.wT1); }
+        else       { s.sT0 += e; s.wT0 = fmaf(t, e, s.wT0); }
+    }
+}
+
+// Close the lane's current tile: fold it into the row sums and, when sampling,
+// enter it into the level-1 race with weight mass / E.
+template <bool kSample>
+__device__ __forceinline__ void close_tile(LaneState& s, int tile, float inv_e, bool nonempty)
+{
+    float sT = s.sT0 + s.sT1;
+    float wT = s.wT0 + s.wT1;
+    s.S += sT;
+    s.W += wT;
+    if (kSample && nonempty) {
+        Cand c{sT * inv_e, tile};
+        if (c.q > s.best.q) s.best = c;
+    }
+    s.sT0 = s.sT1 = s.wT0 = s.wT1 = 0.0f;
+}
+
+// What one wave hands to the workgroup merge.
+struct WavePartial {
+    double S, W;
+    float rc, q;
+    int tile, pad;
+};
+
+template <typename Chunk, int kWaves, bool kSample>
+__global__ __launch_bounds__(kWaves * 64)
+void vocab_pass_kernel(VocabPassArgs a)
+{
+    __shared__ WavePartial partial[kWaves];
+    __shared__ float tile_inv_e[kSample ? kWaves : 1][4][kLanes];
+
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int64_t row = blockIdx.x;
+    const int64_t V = a.V;
+    const char* rowp = static_cast<const char*>(a.logits)
+                     + row * a.row_stride * (int64_t)Chunk::kElemBytes;
+    const float tau = a.tau_rows ? a.tau_rows[row] : a.tau_scalar;
+    const float c = (float)(kLog2e / (double)tau);
+    const uint64_t grow = a.row_base + (uint64_t)row;
+    const uint32_t row_lo = (uint32_t)grow, row_hi = (uint32_t)(grow >> 32);
+    const uint32_t seed_lo = (uint32_t)a.seed, seed_hi = (uint32_t)(a.seed >> 32);
+
+    const int nst = (int)((V + kSuperCols - 1) / kSuperCols);   // super-tiles in a row
+    const int nfull = (int)(V / kSuperCols);                    // of which complete
+
+    LaneState s;
+    s.rc = -INFINITY;
+    s.S = s.W = s.sT0 = s.sT1 = s.wT0 = s.wT1 = 0.0f;
+    s.best = Cand{-1.0f, 0};
+
+    // Rolling prefetch: kAhead sweeps stay requested ahead of the one being consumed
+    // (16 KiB per wave in flight); sweep i lives in buf[i % kAhead].
+    constexpr int kAhead = Chunk::kAhead;
+    Chunk buf[kAhead];
+    const int64_t lane_col = (int64_t)lane * kChunk;
+    if (wave < nfull) {
+#pragma unroll
+        for (int i = 0; i < kAhead; ++i)
+            buf[i].load(rowp, (int64_t)wave * kSuperCols + i * kSweepCols + lane_col);
+    }
+
+    // Tile noise for four of this wave's super-tiles at a time (the k-th to (k+3)-th
+    // it visits): lane l draws the Philox block that serves tiles 4j..4j+3 (j = l % 16)
+    // of the (k + l / 16)-th one.  The table is private to the wave; LDS operations of
+    // one wave complete in order, so a wave-level fence is all the ordering it needs.
+    auto refill_tile_noise = [&](int st_first) {
+        const int st_n = st_first + (lane >> 4) * kWaves;
+        uint32_t w[4];
+        philox4x32_10((uint32_t)(st_n * 16 + (lane & 15)), row_lo, row_hi, 1u, seed_lo, seed_hi, w);
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+            tile_inv_e[kSample ? wave : 0][lane >> 4][(lane & 15) * 4 + j] = 1.0f / exp_variate(w[j]);
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    };
+
+    // Complete super-tiles: wave, wave + kWaves, ...  While another complete one
+    // follows, the sweep kAhead further on is requested as soon as a sweep has been
+    // unpacked, unconditionally, so the loads in flight never drain; the last complete
+    // super-tile runs the same body without reaching into a successor.
+    int k = 0;
+    int st = wave;
+    auto run_super_tile = [&](auto prefetch) {
+        float inv_e = 0.0f;
+        if (kSample) {
+            if ((k & 3) == 0) refill_tile_noise(st);
+            inv_e = tile_inv_e[wave][k & 3][lane];
+        }
+        const int64_t this_base = (int64_t)st * kSuperCols + lane_col;
+        const int64_t next_base = (int64_t)(st + kWaves) * kSuperCols + lane_col;
+#pragma unroll
+        for (int i = 0; i < kDepth; ++i) {
+            float z[8];
+            buf[i % kAhead].unpack(z);
+            if (i + kAhead < kDepth)
+                buf[i % kAhead].load(rowp, this_base + (i + kAhead) * kSweepCols);
+            else if (decltype(prefetch)::value)
+                buf[i % kAhead].load(rowp, next_base + (i + kAhead - kDepth) * kSweepCols);
+            accumulate_chunk<true>(s, z, 0xFFu, c);
+        }
+        close_tile<kSample>(s, st * kLanes + lane, inv_e, true);
+        st += kWaves;
+        ++k;
+    };
+    while (st + kWaves < nfull) run_super_tile(std::true_type{});
+    if (st < nfull) run_super_tile(std::false_type{});
+
+    // The one incomplete super-tile of the row, if any, belongs to the wave whose turn
+    // it is; k already counts the super-tiles that wave has done.
+    if (nst > nfull && wave == nfull % kWaves) {
+        st = nfull;
+        float inv_e = 0.0f;
+        if (kSample) {
+            if ((k & 3) == 0) refill_tile_noise(st);
+            inv_e = tile_inv_e[wave][k & 3][lane];
+        }
+        const int64_t base = (int64_t)st * kSuperCols + lane_col;
+        Chunk rb[kDepth];
+        bool any_valid = false;
+        // guarded whole-chunk loads, all issued before the first is consumed
+#pragma unroll
+        for (int i = 0; i < kDepth; ++i)
+            if (base + i * kSweepCols + kChunk <= V) rb[i].load(rowp, base + i * kSweepCols);
+#pragma unroll
+        for (int i = 0; i < kDepth; ++i) {
+            const int64_t col = base + i * kSweepCols;
+            float z[8];
+            unsigned valid = 0u;
+            if (col + kChunk <= V) {
+                rb[i].unpack(z);
+                valid = 0xFFu;
+            } else {
+#pragma unroll
+                for (int j = 0; j < 8; ++j) {
+                    z[j] = 0.0f;
+                    if (col + j < V) { z[j] = Chunk::load_one(rowp, col + j); valid |= 1u << j; }
+                }
+            }
+            any_valid |= valid != 0u;
+            if (__any(valid != 0u)) accumulate_chunk<false>(s, z, valid, c);
+        }
+        close_tile<kSample>(s, st * kLanes + lane, inv_e, any_valid);
+    }
+
+    // lane -> wave, in fp64 (all lanes of a wave share rc, so plain sums)
+    double Sw = wave_sum((double)s.S);
+    double Ww = wave_sum((double)s.W);
+    Cand wb = wave_best(s.best);
+    if (lane == 0) {
+        partial[wave].S = Sw;
+        partial[wave].W = Ww;
+        partial[wave].rc = s.rc;
+        partial[wave].q = wb.q;
+        partial[wave].tile = wb.idx;
+    }
+    __syncthreads();
+    if (wave != 0) return;
+
+    // wave -> row.  Every lane of wave 0 repeats the same scalar merge.
+    float R = -INFINITY;
+#pragma unroll
+    for (int w = 0; w < kWaves; ++w) R = fmaxf(R, partial[w].rc);
+    double S = 0.0, W = 0.0;
+    double best_q = -1.0;
+    int best_tile = 0;
+#pragma unroll
+    for (int w = 0; w < kWaves; ++w) {
+        const float rcw = partial[w].rc;
+        if (!(rcw > -INFINITY)) continue;                 // wave had no columns
+        const double d = (double)R - (double)rcw;         // integer >= 0
+        const int sh = d > 4000.0 ? -4000 : -(int)d;
+        S += ldexp(partial[w].S, sh);
+        W += ldexp(partial[w].W - d * partial[w].S, sh);
+        if (kSample) {
+            const double q = ldexp((double)partial[w].q, sh);
+            if (q > best_q || (q == best_q && partial[w].tile < best_tile)) {
+                best_q = q;
+                best_tile = partial[w].tile;
+            }
+        }
+    }
+    const double lnS = log(S);
+    const double H = lnS - kLn2 * W / S;
+
+    int64_t tok;
+    if (kSample) {
+        // Level 2: Gumbel-max inside the winning tile, in race form: maximise
+        // 2^{(z - zmax) c} / E_col.  32 lanes x 4 consecutive columns cover the tile.
+        const int st = best_tile / kLanes, slot = best_tile % kLanes;
+        const int64_t col0 = (int64_t)st * kSuperCols + (int64_t)(lane >> 1) * kSweepCols
+                           + (int64_t)slot * kChunk + (lane & 1) * 4;
+        float z[4];
+        bool ok[4];
+        float zmax = -INFINITY;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            ok[j] = lane < 32 && (col0 + j) < V;
+            z[j] = ok[j] ? Chunk::load_one(rowp, col0 + j) : -INFINITY;
+            zmax = fmaxf(zmax, z[j]);
+        }
+        zmax = wave_max(zmax);
+        uint32_t w[4];
+        philox4x32_10((uint32_t)(col0 >> 2), row_lo, row_hi, 2u, seed_lo, seed_hi, w);
+        Cand cb{-1.0f, (int)((int64_t)st * kSuperCols + (int64_t)slot * kChunk)};
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            float q = __builtin_amdgcn_exp2f((z[j] - zmax) * c) / exp_variate(w[j]);
+            Cand cj{ok[j] ? q : -1.0f, (int)(col0 + j)};
+            cb = better(cb, cj);
+        }
+        cb = wave_best(cb);
+        tok = cb.idx;
+        if (tok < 0 || tok >= V) tok = 0;                 // only reachable with NaN input
+        if (lane == 0) a.token_out[row] = (int32_t)tok;
+    } else {
+        tok = a.target_ids ? (int64_t)a.target_ids[row] : -1;
+    }
+
+    if (lane == 0) {
+        if (a.entropy_out) a.entropy_out[row] = (float)H;
+        if (a.logp_out) {
+            float lp = __builtin_nanf("");
+            if (tok >= 0 && tok < V) {
+                const double zt = (double)Chunk::load_one(rowp, tok);
+                lp = (float)((zt * (double)c - (double)R) * kLn2 - lnS);
+            }
+            a.logp_out[row] = lp;
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Batch entropy sum for the scheduler's H_t (mean entropy of the current step,
+// Eq. 4): one workgroup, fp64, fixed summation order.
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(1024)
+void entropy_reduce_kernel(const float* __restrict__ entropy, const uint8_t* __restrict__ mask,
+                           int64_t rows, double* sum_out, int64_t* count_out)
+{
+    __shared__ double ssum[16];
+    __shared__ long long scnt[16];
+    double acc = 0.0;
+    long long cnt = 0;
+    for (int64_t r = threadIdx.x; r < rows; r += 1024) {
+        if (!mask || mask[r]) { acc += (double)entropy[r]; ++cnt; }
+    }
+    acc = wave_sum(acc);
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) cnt += __shfl_xor(cnt, off, 64);
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    if (lane == 0) { ssum[wave] = acc; scnt[wave] = cnt; }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        double t = 0.0;
+        long long n = 0;
+        for (int w = 0; w < 16; ++w) { t += ssum[w]; n += scnt[w]; }
+        if (sum_out) *sum_out = t;
+        if (count_out) *count_out = (int64_t)n;
+    }
+}
+
+// ---------------------------------------------------------------------------
+// host-side launchers
+// ---------------------------------------------------------------------------
+template <typename Chunk, bool kSample>
+static hipError_t launch_rows(const VocabPassArgs& a, hipStream_t stream)
+{
+    constexpr int kWaves = 4;
+    dim3 grid((unsigned)a.rows), block(kWaves * 64);
+    hipLaunchKernelGGL((vocab_pass_kernel<Chunk, kWaves, kSample>), grid, block, 0, stream, a);
+    return hipGetLastError();
+}
+
+hipError_t launch_vocab_pass(const VocabPassArgs& a, bool is_bf16, bool sample, hipStream_t stream)
+{
+    if (a.rows == 0) return hipSuccess;
+    if (is_bf16)
+        return sample ? launch_rows<ChunkBf16, true>(a, stream)
+                      : launch_rows<ChunkBf16, false>(a, stream);
+    return sample ? launch_rows<ChunkF32, true>(a, stream)
+                  : launch_rows<ChunkF32, false>(a, stream);
+}
+
+hipError_t launch_entropy_reduce(const float* entropy, const uint8_t* mask, int64_t rows,
+                                 double* sum_out, int64_t* count_out, hipStream_t stream)
+{
+    hipLaunchKernelGGL(entropy_reduce_kernel, dim3(1), dim3(1024), 0, stream,
+                       entropy, mask, rows, sum_out, count_out);
+    return hipGetLastError();
+}
+
+}  // namespace e3

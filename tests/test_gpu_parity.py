@@ -1,0 +1,275 @@
+"""Parity of the HIP library against the CPU oracle, element by element, on the same
+seeded inputs (needs a GPU; everything goes through the C ABI).
+
+Tolerances (derived in the design doc):
+  * tokens: identical, except rows the oracle flags as near-ties (top-two perturbed
+    scores within 1e-5 relative at either level); the mismatch count is printed;
+  * entropy and log-prob: |x - ref| <= 1e-4 * max(|ref|, 1e-3)  (1e-4 relative with an
+    absolute floor of 1e-7, the resolution of fp32 accumulation near S = 1);
+  * advantages: 1e-6 absolute;
+  * batch entropy sum: equal to the fp64 sum of the library's own fp32 entropies to
+    1e-12 relative, and to the oracle's sum within 1e-6 relative.
+"""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+import paper_2505_18573_amd as e3
+from oracle import e3_oracle as o
+from paper_2505_18573_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+NT = 16          # oracle threads (rows are independent)
+V_Q = 151_936
+
+
+def close(x, ref, rel=1e-4, floor=1e-3):
+    x = np.asarray(x, dtype=np.float64)
+    return np.abs(x - ref) <= rel * np.maximum(np.abs(ref), floor)
+
+
+def assert_close(x, ref, what):
+    ok = close(x, ref)
+    if not ok.all():
+        bad = np.flatnonzero(~ok)[:5]
+        raise AssertionError(f"{what}: {(~ok).sum()} of {ok.size} outside tolerance; first "
+                             f"rows {bad.tolist()} got {np.asarray(x)[bad]} want {ref[bad]}")
+    below_floor = int((np.abs(ref) < 1e-3).sum())
+    return below_floor
+
+
+def check_sample(logits, tau_rows, tau_scalar, seed, row_base, label):
+    """Run both sides on `logits` (device tensor); assert parity; return stats."""
+    tok, logp, ent = e3.e3_sample_entropy(logits, tau_rows, tau_scalar, seed, row_base)
+    torch.cuda.synchronize()
+    ref = o.sample_entropy(wl.host_bits(logits),
+                           None if tau_rows is None else tau_rows.cpu().numpy(),
+                           tau_scalar, seed, row_base, nthreads=NT)
+    tok = tok.cpu().numpy()
+    assert ((tok >= 0) & (tok < logits.shape[1])).all()
+    diff = tok != ref.token
+    unexplained = diff & (ref.near_tie == 0)
+    print(f"[{label}] rows={tok.size} near_tie={int(ref.near_tie.sum())} "
+          f"token mismatches={int(diff.sum())} (unexplained {int(unexplained.sum())})")
+    assert not unexplained.any(), f"{label}: rows {np.flatnonzero(unexplained)[:8]} differ"
+    nfloor = assert_close(ent.cpu().numpy(), ref.entropy, f"{label} entropy")
+    same = ~diff
+    assert_close(logp.cpu().numpy()[same], ref.logp[same], f"{label} logp")
+    # rows where a near-tie went the other way: logp must still be that token's own logp
+    if diff.any():
+        alt = o.logprob_entropy(wl.host_bits(logits)[diff], tok[diff], None,
+                                None if tau_rows is None else tau_rows.cpu().numpy()[diff],
+                                tau_scalar)
+        assert_close(logp.cpu().numpy()[diff], alt.logp, f"{label} logp (near-tie rows)")
+    print(f"[{label}] entropy rows under the 1e-3 floor: {nfloor}")
+    return ref, tok
+
+
+def check_logprob(logits, targets, mask, tau_rows, tau_scalar, label, rows_subset=None):
+    logp, ent, s, n = e3.e3_logprob_entropy(logits, targets, mask, tau_rows, tau_scalar)
+    torch.cuda.synchronize()
+    sel = slice(None) if rows_subset is None else rows_subset
+    sub = logits if rows_subset is None else logits[torch.as_tensor(rows_subset, device=logits.device)]
+    pick = (lambda t: None if t is None else t.cpu().numpy()[sel])
+    ref = o.logprob_entropy(wl.host_bits(sub), pick(targets), pick(mask), pick(tau_rows),
+                            tau_scalar, nthreads=NT)
+    assert_close(ent.cpu().numpy()[sel], ref.entropy, f"{label} entropy")
+    if targets is not None:
+        got = logp.cpu().numpy()[sel]
+        nan_ref = np.isnan(ref.logp)
+        assert np.array_equal(np.isnan(got), nan_ref)
+        assert_close(got[~nan_ref], ref.logp[~nan_ref], f"{label} logp")
+    # batch sum: against the library's own per-row output (all rows) ...
+    keep = torch.ones_like(ent, dtype=torch.bool) if mask is None else mask.bool()
+    own = ent.double()[keep].sum().item()
+    assert s.item() == pytest.approx(own, rel=1e-12, abs=1e-12)
+    assert n.item() == int(keep.sum().item())
+    # ... and against the oracle when it saw every row
+    if rows_subset is None:
+        assert n.item() == ref.entropy_count
+        assert s.item() == pytest.approx(ref.entropy_sum, rel=1e-6, abs=1e-9)
+    return ref
+
+
+# ---------------------------------------------------------------- config 1
+def test_config1_tiny():
+    w = wl.tiny(DEV)
+    ref, tok = check_sample(w.logits, None, 1.0, seed=0, row_base=0, label="cfg1 sample")
+    check_logprob(w.logits, w.target_ids, None, None, 1.0, "cfg1 logprob")
+    adv = e3.e3_grpo_advantages(w.rewards, w.group_offsets)
+    want = o.grpo_advantages(w.rewards.cpu().numpy(), w.group_offsets.cpu().numpy())
+    assert np.abs(adv.cpu().numpy() - want).max() <= 1e-6
+    # the training-side call on the sampled tokens reproduces the rollout-side logp
+    lp2, ent2, _, _ = e3.e3_logprob_entropy(w.logits, torch.from_numpy(tok).to(DEV), None, None, 1.0)
+    tok1, lp1, ent1 = e3.e3_sample_entropy(w.logits, None, 1.0, 0, 0)
+    assert torch.equal(ent1, ent2) and torch.equal(lp1, lp2)
+
+
+# ------------------------------------------- shapes across tiles and ragged tails
+SHAPES = [(1, 5), (7, 9), (8, 8), (100, 6), (513, 5), (1000, 4), (8192, 4), (8200, 4),
+          (16384 + 24, 3), (20_003, 3), (4 * 8192 + 8, 3), (5 * 8192 - 8, 3), (70_001, 2)]
+
+
+@pytest.mark.parametrize("dtype", [torch.bfloat16, torch.float32])
+@pytest.mark.parametrize("V,rows", SHAPES)
+def test_shapes(V, rows, dtype):
+    g = torch.Generator(device=DEV).manual_seed(V * 31 + rows)
+    esz = 2 if dtype == torch.bfloat16 else 4
+    pitch = -(-V * esz // 16) * 16 // esz + (16 // esz) * (rows % 2)   # aligned, sometimes padded
+    store = (torch.randn((rows, pitch), generator=g, device=DEV) * 3.0).to(dtype)
+    logits = store[:, :V]
+    tau = (0.6 + 0.8 * torch.rand(rows, generator=g, device=DEV)).float()
+    check_sample(logits, tau, 1.0, seed=V, row_base=10_000 + V, label=f"V={V} {dtype}")
+    tgt = torch.randint(0, V, (rows,), generator=g, device=DEV).to(torch.int32)
+    check_logprob(logits, tgt, None, tau, 1.0, f"V={V} {dtype} logprob")
+
+
+def test_full_vocab_row_fp32_and_bf16_ragged_tail():
+    # V = 151,936 = 18 complete super-tiles + 4480 columns: every wave path is exercised
+    g = torch.Generator(device=DEV).manual_seed(77)
+    x = torch.randn((6, V_Q), generator=g, device=DEV) * 3.0
+    x[0, V_Q - 1] += 12.0            # winner in the very last column
+    x[1, 0] += 12.0                  # winner in the first
+    x[2, 18 * 8192 + 5] += 12.0      # winner inside the incomplete super-tile
+    for dtype in (torch.float32, torch.bfloat16):
+        lg = x.to(dtype)
+        ref, tok = check_sample(lg, None, 0.7, seed=5, row_base=1 << 40, label=f"full row {dtype}")
+        assert tok[0] == V_Q - 1 or ref.logp[0] < -1e-3
+
+
+# ---------------------------------------------------------------- config 2
+def test_config2_decode_step_full_size():
+    w = wl.decode_step(DEV)
+    assert w.logits.shape == (512, V_Q) and w.logits.dtype == torch.bfloat16
+    check_sample(w.logits, w.tau_rows, 1.0, seed=1, row_base=0, label="cfg2")
+
+
+# ---------------------------------------------------------------- config 3
+def test_config3_dynamic_budgets_full_size():
+    w = wl.dynamic_budgets(DEV)
+    assert w.rows == 1024 and w.group_offsets.shape[0] == 129
+    check_sample(w.logits, w.tau_rows, 1.0, seed=2, row_base=0, label="cfg3")
+    for ddof, eps in ((0, 0.0), (1, 0.0), (0, 1e-6)):
+        adv = e3.e3_grpo_advantages(w.rewards, w.group_offsets, ddof=ddof, eps=eps).cpu().numpy()
+        want = o.grpo_advantages(w.rewards.cpu().numpy(), w.group_offsets.cpu().numpy(),
+                                 ddof=ddof, eps=float(np.float32(eps)))
+        assert np.abs(adv - want).max() <= 1e-6
+        off = w.group_offsets.cpu().numpy()
+        assert (adv[off[0]:off[1]] == 0).all() and (adv[off[1]:off[2]] == 0).all()  # all-0, all-1
+
+
+# ---------------------------------------------------------------- config 4
+def test_config4_training_pass_full_size_sampled_rows():
+    w = wl.training_pass(DEV)                                   # 32,768 x 151,936 bf16, ~10 GB
+    assert w.logits.shape == (32_768, V_Q)
+    subset = np.unique(np.concatenate([np.arange(0, 32_768, 64), [1, 32_767]]))
+    ref = check_logprob(w.logits, w.target_ids, None, None, 1.0, "cfg4", rows_subset=subset)
+    # mean entropy of N(0,3^2) logits at tau = 1 sits near ln V - 9/2
+    assert ref.entropy.mean() == pytest.approx(math.log(V_Q) - 4.5, abs=0.1)
+    del w
+    torch.cuda.empty_cache()
+
+
+def test_config4_reduced_all_rows_with_mask():
+    w = wl.training_pass(DEV, rows=1536, masked_fraction=0.25)
+    check_logprob(w.logits, w.target_ids, w.row_mask, None, 1.0, "cfg4 reduced + mask")
+
+
+# ---------------------------------------------------------------- config 5
+def test_config5_large_decode_full_size():
+    w = wl.large_decode(DEV)
+    assert w.logits.shape == (4096, V_Q)
+    ref, tok = check_sample(w.logits, w.tau_rows, 1.0, seed=4, row_base=0, label="cfg5")
+    tie_rows = w.notes["tie_rows"].cpu().numpy()
+    top2 = torch.topk(w.logits[w.notes["tie_rows"]].float(), 2, dim=1).values
+    gap = (top2[:, 0] - top2[:, 1]).cpu().numpy()
+    print(f"[cfg5] constructed tie rows: {tie_rows.size}, stored gap 0 in {(gap == 0).sum()}, "
+          f"one bf16 ulp in {(gap > 0).sum()}")
+    cold = ref.entropy[0::2]                                    # tau = 0.3 rows
+    print(f"[cfg5] tau=0.3 entropy: min {cold.min():.3e} median {np.median(cold):.3f}")
+
+
+# ---------------------------------------------------------------- edge cases
+def test_delta_model_rows_low_entropy():
+    # Appendix A two-level rows: one logit Delta above the rest; entropy ~1e-1 and below
+    deltas = [14.0, 15.0, 16.0, 17.0, 18.0, 20.0, 24.0, 30.0]
+    lg = wl.delta_model_rows(DEV, deltas, V=V_Q, dtype=torch.float32)
+    ref = check_logprob(lg, torch.tensor([(r * 7919) % V_Q for r in range(len(deltas))],
+                                         dtype=torch.int32, device=DEV),
+                        None, None, 1.0, "delta-model")
+    assert ref.entropy[2] == pytest.approx(0.2859231621, abs=1e-9)
+    check_sample(lg.to(torch.bfloat16), None, 1.0, seed=8, row_base=0, label="delta-model bf16")
+
+
+def test_uniform_rows_and_extreme_temperatures():
+    lg = torch.full((4, V_Q), 2.5, dtype=torch.bfloat16, device=DEV)
+    _, ent, _, _ = e3.e3_logprob_entropy(lg, None, None, None, 1.0)
+    assert np.allclose(ent.cpu().numpy(), math.log(V_Q), rtol=1e-6)
+    g = torch.Generator(device=DEV).manual_seed(3)
+    lg = (torch.randn((8, 30_000), generator=g, device=DEV) * 3).to(torch.bfloat16)
+    tau = torch.tensor([0.05, 0.1, 0.3, 1.0, 2.0, 10.0, 100.0, 1000.0], device=DEV)
+    check_sample(lg, tau, 1.0, seed=9, row_base=0, label="extreme tau")
+    big = (lg.float() * 40.0).to(torch.bfloat16)                # |z| up to ~600
+    check_sample(big, None, 1.0, seed=9, row_base=0, label="large magnitudes")
+    check_sample(lg - 1000.0, None, 1.0, seed=9, row_base=0, label="shifted by -1000")
+
+
+def test_row_base_batching_and_determinism():
+    g = torch.Generator(device=DEV).manual_seed(4)
+    lg = (torch.randn((64, 20_000), generator=g, device=DEV) * 3).to(torch.bfloat16)
+    a = e3.e3_sample_entropy(lg, None, 0.9, seed=12, row_base=500)
+    b = e3.e3_sample_entropy(lg, None, 0.9, seed=12, row_base=500)
+    assert all(torch.equal(x, y) for x, y in zip(a, b))         # bit-reproducible
+    lo = e3.e3_sample_entropy(lg[:32], None, 0.9, seed=12, row_base=500)
+    hi = e3.e3_sample_entropy(lg[32:], None, 0.9, seed=12, row_base=532)
+    assert torch.equal(torch.cat([lo[0], hi[0]]), a[0])
+    c = e3.e3_sample_entropy(lg, None, 0.9, seed=13, row_base=500)
+    assert not torch.equal(c[0], a[0])
+
+
+def test_targets_out_of_range_empty_batch_and_masks():
+    g = torch.Generator(device=DEV).manual_seed(5)
+    lg = (torch.randn((6, 1000), generator=g, device=DEV) * 2).float()
+    tgt = torch.tensor([0, 999, -1, 1000, 5, 2**31 - 1], dtype=torch.int32, device=DEV)
+    mask = torch.tensor([1, 0, 1, 0, 0, 1], dtype=torch.uint8, device=DEV)
+    check_logprob(lg, tgt, mask, None, 1.3, "targets/mask")
+    empty = torch.empty((0, 1000), dtype=torch.float32, device=DEV)
+    lp, ent, s, n = e3.e3_logprob_entropy(empty, torch.empty(0, dtype=torch.int32, device=DEV),
+                                          None, None, 1.0)
+    assert s.item() == 0.0 and n.item() == 0 and ent.numel() == 0
+    tok, _, _ = e3.e3_sample_entropy(empty, None, 1.0, 1)
+    assert tok.numel() == 0
+
+
+def test_sample_frequencies_on_gpu_follow_softmax():
+    # chi-square of the library's own draws (same row, 200k different global row ids)
+    from scipy.stats import chisquare
+    z = torch.tensor(np.random.default_rng(1).normal(0, 2, 64), dtype=torch.float32)
+    n = 200_000
+    lg = z.repeat(n, 1).to(DEV)
+    tok, _, _ = e3.e3_sample_entropy(lg, None, 0.8, seed=21, row_base=0)
+    p = np.exp(o.log_softmax_row(z.numpy(), 0.8))
+    counts = np.bincount(tok.cpu().numpy(), minlength=64).astype(float)
+    exp = p * n
+    small = exp < 5
+    counts = np.append(counts[~small], counts[small].sum())
+    exp = np.append(exp[~small], exp[small].sum())
+    assert chisquare(counts, exp)[1] > 1e-4
+
+
+def test_advantages_group_shapes():
+    sizes = [1, 2, 3, 0, 64, 65, 200, 0, 7, 1000]
+    off = torch.tensor(np.concatenate([[0], np.cumsum(sizes)]), dtype=torch.int32, device=DEV)
+    g = torch.Generator(device=DEV).manual_seed(6)
+    r = torch.randn(int(off[-1]), generator=g, device=DEV)
+    r[off[5]:off[6]] = 0.25                                     # a constant group of 65
+    for ddof in (0, 1):
+        adv = e3.e3_grpo_advantages(r, off, ddof=ddof).cpu().numpy()
+        want = o.grpo_advantages(r.cpu().numpy(), off.cpu().numpy(), ddof=ddof)
+        assert np.abs(adv - want).max() <= 1e-6
+    none = e3.e3_grpo_advantages(torch.empty(0, device=DEV),
+                                 torch.zeros(1, dtype=torch.int32, device=DEV))
+    assert none.numel() == 0
