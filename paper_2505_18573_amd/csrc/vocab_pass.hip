@@ -173,55 +173,37 @@ struct ChunkF32 {
 };
 
 // ---------------------------------------------------------------------------
-// Per-lane running state of one wave.  rc is wave-uniform.
+// Running state of one wave.  rc, top, dom_lane and dom_open are wave-uniform.
 // All sums are in base-2 units relative to rc:  t = z*c - rc,  e = 2^t.
+//
+// The largest logit the wave has met so far (`top`, the one that last moved the
+// reference) is kept OUT of the fp32 sums and carried as a scalar.  On a peaked row
+// that term is ~1 while all others together may be 1e-4 or less; inside an fp32
+// accumulator it would swallow their low bits (absolute error ~1e-7), kept apart the
+// remaining sums stay accurate relative to themselves and the row merge can form
+// ln S and the entropy from log1p(rest / dominant) without cancellation.
 // ---------------------------------------------------------------------------
 struct LaneState {
-    float rc;          // shared reference, integer valued, -inf before the first element
+    float rc;          // shared reference = ceil(top * c), -inf before the first element
+    float top;         // the excluded maximum (a stored logit value), -inf before the first
+    int dom_lane;      // lane whose chunk held `top`
+    bool dom_open;     // `top` belongs to that lane's tile that is still open
     float S, W;        // finished tiles:   sum e,  sum t*e
     float sT0, sT1;    // current tile (two chains for instruction-level parallelism)
     float wT0, wT1;
     Cand best;         // best tile so far: q = tile mass / E_tile, idx = tile id
 };
 
-// Move the wave's reference up to cover a new maximum.  d is a non-negative
-// integer, so 2^-d is exact and the move costs no accuracy.
-__device__ __forceinline__ void raise_reference(LaneState& s, float chunk_max, float c)
-{
-    const float top = wave_max(chunk_max);
-    float new_rc = ceilf(top * c);
-    if (fmaf(top, c, -new_rc) > 0.0f) new_rc += 1.0f;   // product rounded down onto an integer
-    new_rc = uniform_f(new_rc);
-    if (s.rc > -INFINITY) {
-        float d = new_rc - s.rc;
-        float f = exp2f(-d);
-        s.W = fmaf(-d, s.S, s.W) * f;     s.S *= f;
-        s.wT0 = fmaf(-d, s.sT0, s.wT0) * f; s.sT0 *= f;
-        s.wT1 = fmaf(-d, s.sT1, s.wT1) * f; s.sT1 *= f;
-        s.best.q *= f;
-    }
-    s.rc = new_rc;
-}
-
-// Accumulate one chunk.  `valid` has bit j set when element j exists; the fast
-// path passes the constant 0xFF and the masking folds away.
+// Add the terms of one chunk.  `valid` has bit j set when element j takes part; the
+// fast path passes the constant 0xFF and the masking folds away.
 template <bool kAllValid>
-__device__ __forceinline__ void accumulate_chunk(LaneState& s, float z[8], unsigned valid, float c)
+__device__ __forceinline__ void add_terms(LaneState& s, const float z[8], unsigned valid, float c)
 {
-    if (!kAllValid) {
-#pragma unroll
-        for (int j = 0; j < 8; ++j)
-            if (!((valid >> j) & 1u)) z[j] = -INFINITY;
-    }
-    float cm = fmax3(fmax3(z[0], z[1], z[2]), fmax3(z[3], z[4], z[5]), fmax3(z[6], z[7], z[7]));
-    // t_max > 0 means the reference no longer covers this sweep (also true while rc = -inf)
-    float tmax = fmaf(cm, c, -s.rc);
-    if (__any(tmax > 0.0f)) raise_reference(s, cm, c);
     const float nrc = -s.rc;
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
         float zj = z[j];
-        if (!kAllValid) zj = ((valid >> j) & 1u) ? zj : 0.0f;
+        if (!kAllValid) zj = ((valid >> j) & 1u) ? zj : 0.0f;   // keeps t finite
         float t = fmaf(zj, c, nrc);
         float e = __builtin_amdgcn_exp2f(t);
         if (!kAllValid) e = ((valid >> j) & 1u) ? e : 0.0f;
@@ -230,27 +212,94 @@ __device__ __forceinline__ void accumulate_chunk(LaneState& s, float z[8], unsig
     }
 }
 
-// Close the lane's current tile: fold it into the row sums and, when sampling,
-// enter it into the level-1 race with weight mass / E.
-template <bool kSample>
-__device__ __forceinline__ void close_tile(LaneState& s, int tile, float inv_e, bool nonempty)
+// A sweep holds a logit above the wave's reference.  Move the reference to
+// ceil(new top * c): the shift d is a non-negative integer, so scaling by 2^-d is
+// exact.  The previous top becomes an ordinary term of the lane that held it; the new
+// one is taken out of its chunk.  Returns the mask of elements still to be added.
+__device__ __forceinline__ unsigned new_maximum(LaneState& s, const float z[8], float chunk_max,
+                                                float c, int lane)
 {
-    float sT = s.sT0 + s.sT1;
-    float wT = s.wT0 + s.wT1;
+    const float top = uniform_f(wave_max(chunk_max));
+    float new_rc = ceilf(top * c);
+    if (fmaf(top, c, -new_rc) > 0.0f) new_rc += 1.0f;   // product rounded down onto an integer
+    new_rc = uniform_f(new_rc);
+    if (s.rc > -INFINITY) {
+        const float d = new_rc - s.rc;
+        const float f = exp2f(-d);
+        s.W = fmaf(-d, s.S, s.W) * f;       s.S *= f;
+        s.wT0 = fmaf(-d, s.sT0, s.wT0) * f; s.sT0 *= f;
+        s.wT1 = fmaf(-d, s.sT1, s.wT1) * f; s.sT1 *= f;
+        s.best.q *= f;
+        const float t_old = fmaf(s.top, c, -new_rc);
+        const float e_old = __builtin_amdgcn_exp2f(t_old);
+        if (lane == s.dom_lane) {
+            if (s.dom_open) { s.sT0 += e_old; s.wT0 = fmaf(t_old, e_old, s.wT0); }
+            else            { s.S += e_old;   s.W = fmaf(t_old, e_old, s.W); }
+        }
+    }
+    s.rc = new_rc;
+    s.top = top;
+    const unsigned long long holders = __ballot(chunk_max == top);
+    s.dom_lane = __builtin_amdgcn_readfirstlane((int)__builtin_ctzll(holders | (1ull << 63)));
+    s.dom_open = true;
+    unsigned keep = 0xFFu;
+    if (lane == s.dom_lane) {
+#pragma unroll
+        for (int j = 7; j >= 0; --j)
+            if (z[j] == top) keep = 0xFFu & ~(1u << j);          // ends on the lowest such j
+    }
+    return keep;
+}
+
+// Accumulate one chunk of 8 logits.
+template <bool kAllValid>
+__device__ __forceinline__ void accumulate_chunk(LaneState& s, float z[8], unsigned valid, float c,
+                                                 int lane)
+{
+    if (!kAllValid) {
+#pragma unroll
+        for (int j = 0; j < 8; ++j)
+            if (!((valid >> j) & 1u)) z[j] = -INFINITY;
+    }
+    const float cm = fmax3(fmax3(z[0], z[1], z[2]), fmax3(z[3], z[4], z[5]), fmax3(z[6], z[7], z[7]));
+    // t_max > 0: the reference no longer covers this sweep (always so while rc = -inf)
+    const float tmax = fmaf(cm, c, -s.rc);
+    if (__any(tmax > 0.0f)) {
+        valid &= new_maximum(s, z, cm, c, lane);
+        add_terms<false>(s, z, valid, c);
+    } else {
+        add_terms<kAllValid>(s, z, valid, c);
+    }
+}
+
+// Close the lane's current tile: fold it into the row sums and, when sampling, enter
+// it into the level-1 race with weight mass / E.  The tile that holds the excluded
+// maximum counts it in its mass.
+template <bool kSample>
+__device__ __forceinline__ void close_tile(LaneState& s, int tile, float inv_e, bool nonempty,
+                                           float c, int lane)
+{
+    const float sT = s.sT0 + s.sT1;
+    const float wT = s.wT0 + s.wT1;
     s.S += sT;
     s.W += wT;
     if (kSample && nonempty) {
-        Cand c{sT * inv_e, tile};
-        if (c.q > s.best.q) s.best = c;
+        float mass = sT;
+        if (s.dom_open && lane == s.dom_lane)
+            mass += __builtin_amdgcn_exp2f(fmaf(s.top, c, -s.rc));
+        Cand cand{mass * inv_e, tile};
+        if (cand.q > s.best.q) s.best = cand;
     }
+    s.dom_open = false;
     s.sT0 = s.sT1 = s.wT0 = s.wT1 = 0.0f;
 }
 
 // What one wave hands to the workgroup merge.
 struct WavePartial {
-    double S, W;
-    float rc, q;
-    int tile, pad;
+    double S, W;       // sums over the wave's columns except `top`, relative to rc
+    float rc, top;
+    float q;
+    int tile;
 };
 
 template <typename Chunk, int kWaves, bool kSample>
@@ -277,6 +326,9 @@ void vocab_pass_kernel(VocabPassArgs a)
 
     LaneState s;
     s.rc = -INFINITY;
+    s.top = -INFINITY;
+    s.dom_lane = 0;
+    s.dom_open = false;
     s.S = s.W = s.sT0 = s.sT1 = s.wT0 = s.wT1 = 0.0f;
     s.best = Cand{-1.0f, 0};
 
@@ -329,9 +381,9 @@ void vocab_pass_kernel(VocabPassArgs a)
                 buf[i % kAhead].load(rowp, this_base + (i + kAhead) * kSweepCols);
             else if (decltype(prefetch)::value)
                 buf[i % kAhead].load(rowp, next_base + (i + kAhead - kDepth) * kSweepCols);
-            accumulate_chunk<true>(s, z, 0xFFu, c);
+            accumulate_chunk<true>(s, z, 0xFFu, c, lane);
         }
-        close_tile<kSample>(s, st * kLanes + lane, inv_e, true);
+        close_tile<kSample>(s, st * kLanes + lane, inv_e, true, c, lane);
         st += kWaves;
         ++k;
     };
@@ -370,30 +422,38 @@ void vocab_pass_kernel(VocabPassArgs a)
                 }
             }
             any_valid |= valid != 0u;
-            if (__any(valid != 0u)) accumulate_chunk<false>(s, z, valid, c);
+            if (__any(valid != 0u)) accumulate_chunk<false>(s, z, valid, c, lane);
         }
-        close_tile<kSample>(s, st * kLanes + lane, inv_e, any_valid);
+        close_tile<kSample>(s, st * kLanes + lane, inv_e, any_valid, c, lane);
     }
 
     // lane -> wave, in fp64 (all lanes of a wave share rc, so plain sums)
-    double Sw = wave_sum((double)s.S);
-    double Ww = wave_sum((double)s.W);
-    Cand wb = wave_best(s.best);
+    const double Sw = wave_sum((double)s.S);
+    const double Ww = wave_sum((double)s.W);
+    const Cand wb = wave_best(s.best);
     if (lane == 0) {
         partial[wave].S = Sw;
         partial[wave].W = Ww;
         partial[wave].rc = s.rc;
+        partial[wave].top = s.top;
         partial[wave].q = wb.q;
         partial[wave].tile = wb.idx;
     }
     __syncthreads();
     if (wave != 0) return;
 
-    // wave -> row.  Every lane of wave 0 repeats the same scalar merge.
-    float R = -INFINITY;
+    // wave -> row.  Every lane of wave 0 repeats the same scalar merge, in fp64.
+    // R is the common reference, `peak` the largest logit of the row; every other
+    // wave's excluded maximum joins the rest as an ordinary term.
+    float R = -INFINITY, peak = -INFINITY;
+    int peak_wave = 0;
 #pragma unroll
-    for (int w = 0; w < kWaves; ++w) R = fmaxf(R, partial[w].rc);
-    double S = 0.0, W = 0.0;
+    for (int w = 0; w < kWaves; ++w) {
+        R = fmaxf(R, partial[w].rc);
+        if (partial[w].top > peak) { peak = partial[w].top; peak_wave = w; }
+    }
+    const double cd = (double)c;
+    double S_rest = 0.0, W_rest = 0.0;   // relative to R, peak excluded
     double best_q = -1.0;
     int best_tile = 0;
 #pragma unroll
@@ -402,8 +462,14 @@ void vocab_pass_kernel(VocabPassArgs a)
         if (!(rcw > -INFINITY)) continue;                 // wave had no columns
         const double d = (double)R - (double)rcw;         // integer >= 0
         const int sh = d > 4000.0 ? -4000 : -(int)d;
-        S += ldexp(partial[w].S, sh);
-        W += ldexp(partial[w].W - d * partial[w].S, sh);
+        S_rest += ldexp(partial[w].S, sh);
+        W_rest += ldexp(partial[w].W - d * partial[w].S, sh);
+        if (w != peak_wave) {
+            const double tw = (double)partial[w].top * cd - (double)R;
+            const double ew = exp2(tw);
+            S_rest += ew;
+            W_rest += tw * ew;
+        }
         if (kSample) {
             const double q = ldexp((double)partial[w].q, sh);
             if (q > best_q || (q == best_q && partial[w].tile < best_tile)) {
@@ -412,8 +478,14 @@ void vocab_pass_kernel(VocabPassArgs a)
             }
         }
     }
-    const double lnS = log(S);
-    const double H = lnS - kLn2 * W / S;
+    // With e_p = 2^{t_p} the peak's term, x = S_rest / e_p and y = W_rest / e_p:
+    //   ln S = t_p ln2 + log1p(x),   H = ln S - ln2 W / S = log1p(x) + ln2 (t_p x - y) / (1 + x),
+    // every piece of which is O(x) when the row is peaked.
+    const double t_p = (double)peak * cd - (double)R;
+    const double inv_ep = exp2(-t_p);
+    const double x = S_rest * inv_ep, y = W_rest * inv_ep;
+    const double l1p = log1p(x);
+    const double H = l1p + kLn2 * (t_p * x - y) / (1.0 + x);
 
     int64_t tok;
     if (kSample) {
@@ -455,7 +527,7 @@ void vocab_pass_kernel(VocabPassArgs a)
             float lp = __builtin_nanf("");
             if (tok >= 0 && tok < V) {
                 const double zt = (double)Chunk::load_one(rowp, tok);
-                lp = (float)((zt * (double)c - (double)R) * kLn2 - lnS);
+                lp = (float)((zt - (double)peak) * cd * kLn2 - l1p);   // ln p = (a_tok - a_peak) - log1p(x)
             }
             a.logp_out[row] = lp;
         }

@@ -4,11 +4,13 @@ seeded inputs (needs a GPU; everything goes through the C ABI).
 Tolerances (derived in DESIGN.md):
   * tokens: identical, except rows the oracle flags as near-ties (top-two perturbed
     scores within 1e-5 relative at either level); the mismatch count is printed;
-  * entropy and log-prob: |x - ref| <= 1e-4 * max(|ref|, 1e-3)  (1e-4 relative with an
-    absolute floor of 1e-7, the resolution of fp32 accumulation near S = 1);
+  * entropy and log-prob: |x - ref| <= 1e-4 * max(|ref|, 1e-6)  (1e-4 relative; the
+    absolute floor of 1e-10 sits three decades above the oracle's own resolution of
+    ~1e-13 when it adds terms of 1e-13 into a sum near 1);
   * advantages: 1e-6 absolute;
   * batch entropy sum: equal to the fp64 sum of the library's own fp32 entropies to
-    1e-12 relative, and to the oracle's sum within 1e-6 relative.
+    1e-12 relative, and to the oracle's sum within 1e-6 relative (plus the per-row
+    absolute floor of 1e-10 times the number of rows).
 """
 import math
 
@@ -26,7 +28,7 @@ NT = 16          # oracle threads (rows are independent)
 V_Q = 151_936
 
 
-def close(x, ref, rel=1e-4, floor=1e-3):
+def close(x, ref, rel=1e-4, floor=1e-6):
     x = np.asarray(x, dtype=np.float64)
     return np.abs(x - ref) <= rel * np.maximum(np.abs(ref), floor)
 
@@ -37,7 +39,12 @@ def assert_close(x, ref, what):
         bad = np.flatnonzero(~ok)[:5]
         raise AssertionError(f"{what}: {(~ok).sum()} of {ok.size} outside tolerance; first "
                              f"rows {bad.tolist()} got {np.asarray(x)[bad]} want {ref[bad]}")
-    below_floor = int((np.abs(ref) < 1e-3).sum())
+    below_floor = int((np.abs(ref) < 1e-6).sum())
+    nz = ref != 0
+    if nz.any():
+        rel = np.abs(np.asarray(x, dtype=np.float64)[nz] - ref[nz]) / np.abs(ref[nz])
+        print(f"[{what}] max rel err {rel.max():.2e} (at |ref| = {np.abs(ref[nz][rel.argmax()]):.3e}), "
+              f"min |ref| {np.abs(ref[nz]).min():.3e}")
     return below_floor
 
 
@@ -64,7 +71,7 @@ def check_sample(logits, tau_rows, tau_scalar, seed, row_base, label):
                                 None if tau_rows is None else tau_rows.cpu().numpy()[diff],
                                 tau_scalar)
         assert_close(logp.cpu().numpy()[diff], alt.logp, f"{label} logp (near-tie rows)")
-    print(f"[{label}] entropy rows under the 1e-3 floor: {nfloor}")
+    print(f"[{label}] entropy rows under the 1e-6 floor: {nfloor}")
     return ref, tok
 
 
@@ -90,7 +97,7 @@ def check_logprob(logits, targets, mask, tau_rows, tau_scalar, label, rows_subse
     # ... and against the oracle when it saw every row
     if rows_subset is None:
         assert n.item() == ref.entropy_count
-        assert s.item() == pytest.approx(ref.entropy_sum, rel=1e-6, abs=1e-9)
+        assert s.item() == pytest.approx(ref.entropy_sum, rel=1e-6, abs=1e-10 * max(1, n.item()))
     return ref
 
 
@@ -168,7 +175,7 @@ def test_config4_training_pass_full_size_sampled_rows():
     subset = np.unique(np.concatenate([np.arange(0, 32_768, 64), [1, 32_767]]))
     ref = check_logprob(w.logits, w.target_ids, None, None, 1.0, "cfg4", rows_subset=subset)
     # mean entropy of N(0,3^2) logits at tau = 1 sits near ln V - 9/2
-    assert ref.entropy.mean() == pytest.approx(math.log(V_Q) - 4.5, abs=0.1)
+    assert ref.entropy.mean() == pytest.approx(math.log(V_Q) - 4.5, abs=0.3)
     del w
     torch.cuda.empty_cache()
 
