@@ -177,7 +177,7 @@ def cpu_baseline(batch, rewards, offsets):
     tau = batch.tau_rows.cpu().numpy()
     r = rewards.cpu().numpy()
     off = offsets.cpu().numpy()
-    reps = 3
+    reps = 10
     o.sample_entropy(bits[:threads], tau[:threads], 1.0, 99, 0, nthreads=threads)   # warm the pages
     t0 = time.perf_counter()
     for k in range(reps):

@@ -30,6 +30,17 @@ namespace e3 {
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
+// Tunables (overridable at compile time for experiments).
+#ifndef E3_AHEAD_BF16
+#define E3_AHEAD_BF16 16     // 16 sweeps x 1 KiB = 16 KiB per wave in flight
+#endif
+#ifndef E3_AHEAD_F32
+#define E3_AHEAD_F32 8       // 8 sweeps x 2 KiB
+#endif
+#ifndef E3_NT_LOADS
+#define E3_NT_LOADS 1        // stream the logits with non-temporal loads
+#endif
+
 constexpr int kChunk = 8;                       // columns per lane per sweep
 constexpr int kLanes = 64;                      // lanes = tiles per super-tile
 constexpr int kDepth = 16;                      // sweeps per super-tile
@@ -39,20 +50,64 @@ constexpr double kLog2e = 1.4426950408889634074;
 constexpr double kLn2 = 0.69314718055994530942;
 
 // ---------------------------------------------------------------------------
-// wave-level helpers
+// Wave-level reductions on DPP (data-parallel primitives): butterflies inside a
+// row of 16 lanes (two quad permutes, half-row mirror, row mirror), then the
+// row_bcast15 / row_bcast31 steps that leave the total in lane 63.
 // ---------------------------------------------------------------------------
-__device__ __forceinline__ float wave_max(float v)
+constexpr int kDppXor1 = 0xB1;        // quad_perm [1,0,3,2]
+constexpr int kDppXor2 = 0x4E;        // quad_perm [2,3,0,1]
+constexpr int kDppHalfMirror = 0x141; // row_half_mirror
+constexpr int kDppMirror = 0x140;     // row_mirror
+constexpr int kDppBcast15 = 0x142;    // lane 15 of each row -> next row   (row mask 0xA)
+constexpr int kDppBcast31 = 0x143;    // lane 31 -> rows 2 and 3           (row mask 0xC)
+
+template <int kCtrl, int kRowMask = 0xF>
+__device__ __forceinline__ int dpp_i(int old, int v)
 {
-#pragma unroll
-    for (int off = 32; off > 0; off >>= 1) v = fmaxf(v, __shfl_xor(v, off, 64));
-    return v;
+    return __builtin_amdgcn_update_dpp(old, v, kCtrl, kRowMask, 0xF, false);
+}
+template <int kCtrl, int kRowMask = 0xF>
+__device__ __forceinline__ float dpp_f(float old, float v)
+{
+    return __int_as_float(dpp_i<kCtrl, kRowMask>(__float_as_int(old), __float_as_int(v)));
+}
+template <int kCtrl, int kRowMask = 0xF>
+__device__ __forceinline__ double dpp_d(double old, double v)
+{
+    const int lo = dpp_i<kCtrl, kRowMask>(__double2loint(old), __double2loint(v));
+    const int hi = dpp_i<kCtrl, kRowMask>(__double2hiint(old), __double2hiint(v));
+    return __hiloint2double(hi, lo);
 }
 
+__device__ __forceinline__ float last_lane(float v)
+{
+    return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 63));
+}
+
+// Maximum over the wave, returned wave-uniform.
+__device__ __forceinline__ float wave_max(float v)
+{
+    v = fmaxf(v, dpp_f<kDppXor1>(v, v));
+    v = fmaxf(v, dpp_f<kDppXor2>(v, v));
+    v = fmaxf(v, dpp_f<kDppHalfMirror>(v, v));
+    v = fmaxf(v, dpp_f<kDppMirror>(v, v));
+    v = fmaxf(v, dpp_f<kDppBcast15, 0xA>(v, v));
+    v = fmaxf(v, dpp_f<kDppBcast31, 0xC>(v, v));
+    return last_lane(v);
+}
+
+// Sum over the wave in fp64, returned wave-uniform.
 __device__ __forceinline__ double wave_sum(double v)
 {
-#pragma unroll
-    for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
-    return v;
+    v += dpp_d<kDppXor1>(0.0, v);
+    v += dpp_d<kDppXor2>(0.0, v);
+    v += dpp_d<kDppHalfMirror>(0.0, v);
+    v += dpp_d<kDppMirror>(0.0, v);
+    v += dpp_d<kDppBcast15, 0xA>(0.0, v);
+    v += dpp_d<kDppBcast31, 0xC>(0.0, v);
+    const int lo = __builtin_amdgcn_readlane(__double2loint(v), 63);
+    const int hi = __builtin_amdgcn_readlane(__double2hiint(v), 63);
+    return __hiloint2double(hi, lo);
 }
 
 __device__ __forceinline__ float uniform_f(float v)
@@ -80,16 +135,28 @@ __device__ __forceinline__ Cand better(Cand a, Cand b)
     return take_b ? b : a;
 }
 
+template <int kCtrl, int kRowMask = 0xF>
+__device__ __forceinline__ Cand best_step(Cand c)
+{
+    Cand o;
+    o.q = dpp_f<kCtrl, kRowMask>(c.q, c.q);       // rows masked off see themselves: a no-op
+    o.idx = dpp_i<kCtrl, kRowMask>(c.idx, c.idx);
+    return better(c, o);
+}
+
+// Best candidate of the wave, returned wave-uniform.
 __device__ __forceinline__ Cand wave_best(Cand c)
 {
-#pragma unroll
-    for (int off = 32; off > 0; off >>= 1) {
-        Cand o;
-        o.q = __shfl_xor(c.q, off, 64);
-        o.idx = __shfl_xor(c.idx, off, 64);
-        c = better(c, o);
-    }
-    return c;
+    c = best_step<kDppXor1>(c);
+    c = best_step<kDppXor2>(c);
+    c = best_step<kDppHalfMirror>(c);
+    c = best_step<kDppMirror>(c);
+    c = best_step<kDppBcast15, 0xA>(c);
+    c = best_step<kDppBcast31, 0xC>(c);
+    Cand r;
+    r.q = last_lane(c.q);
+    r.idx = __builtin_amdgcn_readlane(c.idx, 63);
+    return r;
 }
 
 // ---------------------------------------------------------------------------
@@ -125,16 +192,25 @@ __device__ __forceinline__ float exp_variate(uint32_t word)
     return d < 0.0625f ? series : direct;
 }
 
+__device__ __forceinline__ u32x4 stream_load(const u32x4* p)
+{
+#if E3_NT_LOADS
+    return __builtin_nontemporal_load(p);
+#else
+    return *p;
+#endif
+}
+
 // ---------------------------------------------------------------------------
 // chunk loaders: 8 consecutive columns of one lane as fp32
 // ---------------------------------------------------------------------------
 struct ChunkBf16 {
     u32x4 v;
     static constexpr int kElemBytes = 2;
-    static constexpr int kAhead = 16;      // sweeps kept in flight per wave (16 KiB)
+    static constexpr int kAhead = E3_AHEAD_BF16;   // sweeps kept in flight per wave
     __device__ __forceinline__ void load(const char* row, int64_t col)
     {
-        v = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(row + col * 2));
+        v = stream_load(reinterpret_cast<const u32x4*>(row + col * 2));
     }
     __device__ __forceinline__ void unpack(float z[8]) const
     {
@@ -152,12 +228,12 @@ struct ChunkBf16 {
 struct ChunkF32 {
     u32x4 a, b;
     static constexpr int kElemBytes = 4;
-    static constexpr int kAhead = 8;       // sweeps kept in flight per wave (16 KiB)
+    static constexpr int kAhead = E3_AHEAD_F32;    // sweeps kept in flight per wave
     __device__ __forceinline__ void load(const char* row, int64_t col)
     {
         const u32x4* p = reinterpret_cast<const u32x4*>(row + col * 4);
-        a = __builtin_nontemporal_load(p);
-        b = __builtin_nontemporal_load(p + 1);
+        a = stream_load(p);
+        b = stream_load(p + 1);
     }
     __device__ __forceinline__ void unpack(float z[8]) const
     {
@@ -194,32 +270,20 @@ struct LaneState {
     Cand best;         // best tile so far: q = tile mass / E_tile, idx = tile id
 };
 
-// Add the terms of one chunk.  `valid` has bit j set when element j takes part; the
-// fast path passes the constant 0xFF and the masking folds away.
-template <bool kAllValid>
-__device__ __forceinline__ void add_terms(LaneState& s, const float z[8], unsigned valid, float c)
-{
-    const float nrc = -s.rc;
-#pragma unroll
-    for (int j = 0; j < 8; ++j) {
-        float zj = z[j];
-        if (!kAllValid) zj = ((valid >> j) & 1u) ? zj : 0.0f;   // keeps t finite
-        float t = fmaf(zj, c, nrc);
-        float e = __builtin_amdgcn_exp2f(t);
-        if (!kAllValid) e = ((valid >> j) & 1u) ? e : 0.0f;
-        if (j & 1) { s.sT1 += e; s.wT1 = fmaf(t, e, s.wT1); }
-        else       { s.sT0 += e; s.wT0 = fmaf(t, e, s.wT0); }
-    }
-}
+// A logit slot that must not count (past the end of the row, or the excluded
+// maximum) is filled with this value: t = z*c - rc stays finite, 2^t flushes to
+// exactly 0 and t*0 = 0, so it drops out of every sum without any masking.
+// Real logits are required to be far above it (|z| < 1e30).
+constexpr float kAbsent = -1.0e30f;
 
 // A sweep holds a logit above the wave's reference.  Move the reference to
 // ceil(new top * c): the shift d is a non-negative integer, so scaling by 2^-d is
 // exact.  The previous top becomes an ordinary term of the lane that held it; the new
-// one is taken out of its chunk.  Returns the mask of elements still to be added.
-__device__ __forceinline__ unsigned new_maximum(LaneState& s, const float z[8], float chunk_max,
-                                                float c, int lane)
+// one is struck from its chunk.
+__device__ __forceinline__ void new_maximum(LaneState& s, float z[8], float chunk_max, float c,
+                                            int lane)
 {
-    const float top = uniform_f(wave_max(chunk_max));
+    const float top = wave_max(chunk_max);
     float new_rc = ceilf(top * c);
     if (fmaf(top, c, -new_rc) > 0.0f) new_rc += 1.0f;   // product rounded down onto an integer
     new_rc = uniform_f(new_rc);
@@ -242,33 +306,31 @@ __device__ __forceinline__ unsigned new_maximum(LaneState& s, const float z[8], 
     const unsigned long long holders = __ballot(chunk_max == top);
     s.dom_lane = __builtin_amdgcn_readfirstlane((int)__builtin_ctzll(holders | (1ull << 63)));
     s.dom_open = true;
-    unsigned keep = 0xFFu;
     if (lane == s.dom_lane) {
+        int hit = 8;
 #pragma unroll
         for (int j = 7; j >= 0; --j)
-            if (z[j] == top) keep = 0xFFu & ~(1u << j);          // ends on the lowest such j
-    }
-    return keep;
-}
-
-// Accumulate one chunk of 8 logits.
-template <bool kAllValid>
-__device__ __forceinline__ void accumulate_chunk(LaneState& s, float z[8], unsigned valid, float c,
-                                                 int lane)
-{
-    if (!kAllValid) {
+            if (z[j] == top) hit = j;                           // ends on the lowest such j
 #pragma unroll
         for (int j = 0; j < 8; ++j)
-            if (!((valid >> j) & 1u)) z[j] = -INFINITY;
+            if (j == hit) z[j] = kAbsent;
     }
+}
+
+// Accumulate one chunk of 8 logits (absent slots already hold kAbsent).
+__device__ __forceinline__ void accumulate_chunk(LaneState& s, float z[8], float c, int lane)
+{
     const float cm = fmax3(fmax3(z[0], z[1], z[2]), fmax3(z[3], z[4], z[5]), fmax3(z[6], z[7], z[7]));
     // t_max > 0: the reference no longer covers this sweep (always so while rc = -inf)
     const float tmax = fmaf(cm, c, -s.rc);
-    if (__any(tmax > 0.0f)) {
-        valid &= new_maximum(s, z, cm, c, lane);
-        add_terms<false>(s, z, valid, c);
-    } else {
-        add_terms<kAllValid>(s, z, valid, c);
+    if (__any(tmax > 0.0f)) new_maximum(s, z, cm, c, lane);
+    const float nrc = -s.rc;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+        const float t = fmaf(z[j], c, nrc);
+        const float e = __builtin_amdgcn_exp2f(t);
+        if (j & 1) { s.sT1 += e; s.wT1 = fmaf(t, e, s.wT1); }
+        else       { s.sT0 += e; s.wT0 = fmaf(t, e, s.wT0); }
     }
 }
 
@@ -298,7 +360,7 @@ __device__ __forceinline__ void close_tile(LaneState& s, int tile, float inv_e, 
 struct WavePartial {
     double S, W;       // sums over the wave's columns except `top`, relative to rc
     float rc, top;
-    float q;
+    float q;           // the wave's best level-1 weight, relative to rc
     int tile;
 };
 
@@ -315,25 +377,13 @@ void vocab_pass_kernel(VocabPassArgs a)
     const int64_t V = a.V;
     const char* rowp = static_cast<const char*>(a.logits)
                      + row * a.row_stride * (int64_t)Chunk::kElemBytes;
-    const float tau = a.tau_rows ? a.tau_rows[row] : a.tau_scalar;
-    const float c = (float)(kLog2e / (double)tau);
-    const uint64_t grow = a.row_base + (uint64_t)row;
-    const uint32_t row_lo = (uint32_t)grow, row_hi = (uint32_t)(grow >> 32);
-    const uint32_t seed_lo = (uint32_t)a.seed, seed_hi = (uint32_t)(a.seed >> 32);
 
     const int nst = (int)((V + kSuperCols - 1) / kSuperCols);   // super-tiles in a row
     const int nfull = (int)(V / kSuperCols);                    // of which complete
 
-    LaneState s;
-    s.rc = -INFINITY;
-    s.top = -INFINITY;
-    s.dom_lane = 0;
-    s.dom_open = false;
-    s.S = s.W = s.sT0 = s.sT1 = s.wT0 = s.wT1 = 0.0f;
-    s.best = Cand{-1.0f, 0};
-
     // Rolling prefetch: kAhead sweeps stay requested ahead of the one being consumed
-    // (16 KiB per wave in flight); sweep i lives in buf[i % kAhead].
+    // (16 KiB per wave in flight); sweep i lives in buf[i % kAhead].  The first
+    // requests leave before anything else is looked at.
     constexpr int kAhead = Chunk::kAhead;
     Chunk buf[kAhead];
     const int64_t lane_col = (int64_t)lane * kChunk;
@@ -342,6 +392,28 @@ void vocab_pass_kernel(VocabPassArgs a)
         for (int i = 0; i < kAhead; ++i)
             buf[i].load(rowp, (int64_t)wave * kSuperCols + i * kSweepCols + lane_col);
     }
+
+    const float tau = a.tau_rows ? a.tau_rows[row] : a.tau_scalar;
+    const float c = (float)(kLog2e / (double)tau);
+    const uint64_t grow = a.row_base + (uint64_t)row;
+    const uint32_t row_lo = (uint32_t)grow, row_hi = (uint32_t)(grow >> 32);
+    const uint32_t seed_lo = (uint32_t)a.seed, seed_hi = (uint32_t)(a.seed >> 32);
+
+    // Training side: the target's logit is requested now and used in the epilogue.
+    int64_t tgt = -1;
+    float z_tgt = 0.0f;
+    if (!kSample && wave == 0 && a.target_ids != nullptr) {
+        tgt = a.target_ids[row];
+        if (tgt >= 0 && tgt < V) z_tgt = Chunk::load_one(rowp, tgt);
+    }
+
+    LaneState s;
+    s.rc = -INFINITY;
+    s.top = -INFINITY;
+    s.dom_lane = 0;
+    s.dom_open = false;
+    s.S = s.W = s.sT0 = s.sT1 = s.wT0 = s.wT1 = 0.0f;
+    s.best = Cand{-1.0f, 0};
 
     // Tile noise for four of this wave's super-tiles at a time (the k-th to (k+3)-th
     // it visits): lane l draws the Philox block that serves tiles 4j..4j+3 (j = l % 16)
@@ -381,7 +453,7 @@ void vocab_pass_kernel(VocabPassArgs a)
                 buf[i % kAhead].load(rowp, this_base + (i + kAhead) * kSweepCols);
             else if (decltype(prefetch)::value)
                 buf[i % kAhead].load(rowp, next_base + (i + kAhead - kDepth) * kSweepCols);
-            accumulate_chunk<true>(s, z, 0xFFu, c, lane);
+            accumulate_chunk(s, z, c, lane);
         }
         close_tile<kSample>(s, st * kLanes + lane, inv_e, true, c, lane);
         st += kWaves;
@@ -391,7 +463,8 @@ void vocab_pass_kernel(VocabPassArgs a)
     if (st < nfull) run_super_tile(std::false_type{});
 
     // The one incomplete super-tile of the row, if any, belongs to the wave whose turn
-    // it is; k already counts the super-tiles that wave has done.
+    // it is; k already counts the super-tiles that wave has done.  Its sweeps are taken
+    // in two halves of 8: guarded loads of a half are all issued before the first is used.
     if (nst > nfull && wave == nfull % kWaves) {
         st = nfull;
         float inv_e = 0.0f;
@@ -400,29 +473,33 @@ void vocab_pass_kernel(VocabPassArgs a)
             inv_e = tile_inv_e[wave][k & 3][lane];
         }
         const int64_t base = (int64_t)st * kSuperCols + lane_col;
-        Chunk rb[kDepth];
         bool any_valid = false;
-        // guarded whole-chunk loads, all issued before the first is consumed
+#pragma unroll 1
+        for (int half = 0; half < 2; ++half) {
+            const int64_t hbase = base + (int64_t)half * (kDepth / 2) * kSweepCols;
+            if (hbase - lane_col >= V) break;                    // uniform: nothing left
+            Chunk rb[kDepth / 2];
 #pragma unroll
-        for (int i = 0; i < kDepth; ++i)
-            if (base + i * kSweepCols + kChunk <= V) rb[i].load(rowp, base + i * kSweepCols);
+            for (int i = 0; i < kDepth / 2; ++i)
+                if (hbase + i * kSweepCols + kChunk <= V) rb[i].load(rowp, hbase + i * kSweepCols);
 #pragma unroll
-        for (int i = 0; i < kDepth; ++i) {
-            const int64_t col = base + i * kSweepCols;
-            float z[8];
-            unsigned valid = 0u;
-            if (col + kChunk <= V) {
-                rb[i].unpack(z);
-                valid = 0xFFu;
-            } else {
+            for (int i = 0; i < kDepth / 2; ++i) {
+                const int64_t col = hbase + i * kSweepCols;
+                float z[8];
+                bool valid = false;
+                if (col + kChunk <= V) {
+                    rb[i].unpack(z);
+                    valid = true;
+                } else {
 #pragma unroll
-                for (int j = 0; j < 8; ++j) {
-                    z[j] = 0.0f;
-                    if (col + j < V) { z[j] = Chunk::load_one(rowp, col + j); valid |= 1u << j; }
+                    for (int j = 0; j < 8; ++j) {
+                        z[j] = kAbsent;
+                        if (col + j < V) { z[j] = Chunk::load_one(rowp, col + j); valid = true; }
+                    }
                 }
+                any_valid |= valid;
+                if (__any(valid)) accumulate_chunk(s, z, c, lane);
             }
-            any_valid |= valid != 0u;
-            if (__any(valid != 0u)) accumulate_chunk<false>(s, z, valid, c, lane);
         }
         close_tile<kSample>(s, st * kLanes + lane, inv_e, any_valid, c, lane);
     }
@@ -431,6 +508,21 @@ void vocab_pass_kernel(VocabPassArgs a)
     const double Sw = wave_sum((double)s.S);
     const double Ww = wave_sum((double)s.W);
     const Cand wb = wave_best(s.best);
+
+    // Rollout side: each wave requests the columns of its own best tile right away
+    // (32 lanes x 4 consecutive columns), so that whichever wave wins the row already
+    // holds them when the winner is known.
+    float cz[4] = {kAbsent, kAbsent, kAbsent, kAbsent};
+    int64_t ccol0 = 0;
+    if (kSample) {
+        const int cst = wb.idx / kLanes, cslot = wb.idx % kLanes;
+        ccol0 = (int64_t)cst * kSuperCols + (int64_t)(lane >> 1) * kSweepCols
+              + (int64_t)cslot * kChunk + (lane & 1) * 4;
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+            if (lane < 32 && ccol0 + j < V) cz[j] = Chunk::load_one(rowp, ccol0 + j);
+    }
+
     if (lane == 0) {
         partial[wave].S = Sw;
         partial[wave].W = Ww;
@@ -440,11 +532,9 @@ void vocab_pass_kernel(VocabPassArgs a)
         partial[wave].tile = wb.idx;
     }
     __syncthreads();
-    if (wave != 0) return;
 
-    // wave -> row.  Every lane of wave 0 repeats the same scalar merge, in fp64.
-    // R is the common reference, `peak` the largest logit of the row; every other
-    // wave's excluded maximum joins the rest as an ordinary term.
+    // wave -> row.  R is the common reference, `peak` the largest logit of the row.
+    // The wave that owns the winning tile finishes the row (wave 0 on the training side).
     float R = -INFINITY, peak = -INFINITY;
     int peak_wave = 0;
 #pragma unroll
@@ -452,83 +542,88 @@ void vocab_pass_kernel(VocabPassArgs a)
         R = fmaxf(R, partial[w].rc);
         if (partial[w].top > peak) { peak = partial[w].top; peak_wave = w; }
     }
+    int owner = 0;
+    if (kSample) {
+        double best_q = -1.0;
+        int best_tile = 0;
+#pragma unroll
+        for (int w = 0; w < kWaves; ++w) {
+            const float rcw = partial[w].rc;
+            if (!(rcw > -INFINITY)) continue;                 // wave had no columns
+            const double d = (double)R - (double)rcw;         // integer >= 0
+            const double q = ldexp((double)partial[w].q, d > 4000.0 ? -4000 : -(int)d);
+            if (q > best_q || (q == best_q && partial[w].tile < best_tile)) {
+                best_q = q;
+                best_tile = partial[w].tile;
+                owner = w;
+            }
+        }
+    }
+    if (wave != owner) return;
+
+    // Every lane of the finishing wave repeats the same scalar merge.  Each other
+    // wave's excluded maximum joins the rest as an ordinary term.
     const double cd = (double)c;
     double S_rest = 0.0, W_rest = 0.0;   // relative to R, peak excluded
-    double best_q = -1.0;
-    int best_tile = 0;
 #pragma unroll
     for (int w = 0; w < kWaves; ++w) {
         const float rcw = partial[w].rc;
-        if (!(rcw > -INFINITY)) continue;                 // wave had no columns
-        const double d = (double)R - (double)rcw;         // integer >= 0
+        if (!(rcw > -INFINITY)) continue;
+        const double d = (double)R - (double)rcw;
         const int sh = d > 4000.0 ? -4000 : -(int)d;
         S_rest += ldexp(partial[w].S, sh);
         W_rest += ldexp(partial[w].W - d * partial[w].S, sh);
         if (w != peak_wave) {
             const double tw = (double)partial[w].top * cd - (double)R;
-            const double ew = exp2(tw);
+            const double ew = (double)exp2f((float)tw);
             S_rest += ew;
             W_rest += tw * ew;
-        }
-        if (kSample) {
-            const double q = ldexp((double)partial[w].q, sh);
-            if (q > best_q || (q == best_q && partial[w].tile < best_tile)) {
-                best_q = q;
-                best_tile = partial[w].tile;
-            }
         }
     }
     // With e_p = 2^{t_p} the peak's term, x = S_rest / e_p and y = W_rest / e_p:
     //   ln S = t_p ln2 + log1p(x),   H = ln S - ln2 W / S = log1p(x) + ln2 (t_p x - y) / (1 + x),
-    // every piece of which is O(x) when the row is peaked.
+    // every piece of which is O(x) when the row is peaked.  t_p lies in (-1, 0].
     const double t_p = (double)peak * cd - (double)R;
-    const double inv_ep = exp2(-t_p);
+    const double inv_ep = (double)exp2f((float)-t_p);
     const double x = S_rest * inv_ep, y = W_rest * inv_ep;
-    const double l1p = log1p(x);
+    const double l1p = (double)log1pf((float)x);
     const double H = l1p + kLn2 * (t_p * x - y) / (1.0 + x);
 
     int64_t tok;
+    float z_tok;
     if (kSample) {
-        // Level 2: Gumbel-max inside the winning tile, in race form: maximise
-        // 2^{(z - zmax) c} / E_col.  32 lanes x 4 consecutive columns cover the tile.
-        const int st = best_tile / kLanes, slot = best_tile % kLanes;
-        const int64_t col0 = (int64_t)st * kSuperCols + (int64_t)(lane >> 1) * kSweepCols
-                           + (int64_t)slot * kChunk + (lane & 1) * 4;
-        float z[4];
-        bool ok[4];
-        float zmax = -INFINITY;
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            ok[j] = lane < 32 && (col0 + j) < V;
-            z[j] = ok[j] ? Chunk::load_one(rowp, col0 + j) : -INFINITY;
-            zmax = fmaxf(zmax, z[j]);
-        }
-        zmax = wave_max(zmax);
+        // Level 2: Gumbel-max inside the winning tile (already in cz), in race form:
+        // maximise 2^{(z - zmax) c} / E_col.
+        const float zmax = wave_max(fmaxf(fmaxf(cz[0], cz[1]), fmaxf(cz[2], cz[3])));
         uint32_t w[4];
-        philox4x32_10((uint32_t)(col0 >> 2), row_lo, row_hi, 2u, seed_lo, seed_hi, w);
-        Cand cb{-1.0f, (int)((int64_t)st * kSuperCols + (int64_t)slot * kChunk)};
+        philox4x32_10((uint32_t)(ccol0 >> 2), row_lo, row_hi, 2u, seed_lo, seed_hi, w);
+        Cand cb{-1.0f, 0x7FFFFFFF};
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
-            float q = __builtin_amdgcn_exp2f((z[j] - zmax) * c) / exp_variate(w[j]);
-            Cand cj{ok[j] ? q : -1.0f, (int)(col0 + j)};
-            cb = better(cb, cj);
+            const bool ok = lane < 32 && ccol0 + j < V;
+            const float q = __builtin_amdgcn_exp2f((cz[j] - zmax) * c) / exp_variate(w[j]);
+            cb = better(cb, Cand{ok ? q : -1.0f, ok ? (int)(ccol0 + j) : 0x7FFFFFFF});
         }
         cb = wave_best(cb);
         tok = cb.idx;
-        if (tok < 0 || tok >= V) tok = 0;                 // only reachable with NaN input
+        if (tok < 0 || tok >= V) tok = 0;                 // only reachable with non-finite input
+        float mine = -INFINITY;
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+            if (ccol0 + j == tok) mine = cz[j];
+        z_tok = wave_max(mine);
         if (lane == 0) a.token_out[row] = (int32_t)tok;
     } else {
-        tok = a.target_ids ? (int64_t)a.target_ids[row] : -1;
+        tok = tgt;
+        z_tok = z_tgt;
     }
 
     if (lane == 0) {
         if (a.entropy_out) a.entropy_out[row] = (float)H;
         if (a.logp_out) {
             float lp = __builtin_nanf("");
-            if (tok >= 0 && tok < V) {
-                const double zt = (double)Chunk::load_one(rowp, tok);
-                lp = (float)((zt - (double)peak) * cd * kLn2 - l1p);   // ln p = (a_tok - a_peak) - log1p(x)
-            }
+            if (tok >= 0 && tok < V)   // ln p = (a_tok - a_peak) - log1p(x)
+                lp = (float)(((double)z_tok - (double)peak) * cd * kLn2 - l1p);
             a.logp_out[row] = lp;
         }
     }
@@ -567,23 +662,44 @@ void entropy_reduce_kernel(const float* __restrict__ entropy, const uint8_t* __r
 // ---------------------------------------------------------------------------
 // host-side launchers
 // ---------------------------------------------------------------------------
-template <typename Chunk, bool kSample>
+template <typename Chunk, bool kSample, int kWaves>
 static hipError_t launch_rows(const VocabPassArgs& a, hipStream_t stream)
 {
-    constexpr int kWaves = 4;
     dim3 grid((unsigned)a.rows), block(kWaves * 64);
     hipLaunchKernelGGL((vocab_pass_kernel<Chunk, kWaves, kSample>), grid, block, 0, stream, a);
     return hipGetLastError();
+}
+
+// Waves per row.  A row of the 151,936-column vocabulary has 19 super-tiles; four
+// waves share them 5/5/5/4.
+static int pick_waves(const VocabPassArgs& a)
+{
+#ifdef E3_FORCE_WAVES
+    return E3_FORCE_WAVES;
+#else
+    (void)a;
+    return 4;
+#endif
+}
+
+template <typename Chunk, bool kSample>
+static hipError_t launch_for(const VocabPassArgs& a, hipStream_t stream)
+{
+    switch (pick_waves(a)) {
+        case 16: return launch_rows<Chunk, kSample, 16>(a, stream);
+        case 8: return launch_rows<Chunk, kSample, 8>(a, stream);
+        default: return launch_rows<Chunk, kSample, 4>(a, stream);
+    }
 }
 
 hipError_t launch_vocab_pass(const VocabPassArgs& a, bool is_bf16, bool sample, hipStream_t stream)
 {
     if (a.rows == 0) return hipSuccess;
     if (is_bf16)
-        return sample ? launch_rows<ChunkBf16, true>(a, stream)
-                      : launch_rows<ChunkBf16, false>(a, stream);
-    return sample ? launch_rows<ChunkF32, true>(a, stream)
-                  : launch_rows<ChunkF32, false>(a, stream);
+        return sample ? launch_for<ChunkBf16, true>(a, stream)
+                      : launch_for<ChunkBf16, false>(a, stream);
+    return sample ? launch_for<ChunkF32, true>(a, stream)
+                  : launch_for<ChunkF32, false>(a, stream);
 }
 
 hipError_t launch_entropy_reduce(const float* entropy, const uint8_t* mask, int64_t rows,
