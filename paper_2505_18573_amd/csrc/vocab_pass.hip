@@ -84,15 +84,25 @@ __device__ __forceinline__ float last_lane(float v)
     return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 63));
 }
 
-// Maximum over the wave, returned wave-uniform.
+// Maximum over the wave, returned wave-uniform.  One DPP-modified v_max_f32 per
+// step (asm, so that no operand canonicalisation is added); the s_nop covers the
+// VALU-write -> DPP-read hazard of this ISA family.
 __device__ __forceinline__ float wave_max(float v)
 {
-    v = fmaxf(v, dpp_f<kDppXor1>(v, v));
-    v = fmaxf(v, dpp_f<kDppXor2>(v, v));
-    v = fmaxf(v, dpp_f<kDppHalfMirror>(v, v));
-    v = fmaxf(v, dpp_f<kDppMirror>(v, v));
-    v = fmaxf(v, dpp_f<kDppBcast15, 0xA>(v, v));
-    v = fmaxf(v, dpp_f<kDppBcast31, 0xC>(v, v));
+    asm("s_nop 1\n\t"
+        "v_max_f32_dpp %0, %0, %0 quad_perm:[1,0,3,2] row_mask:0xf bank_mask:0xf\n\t"
+        "s_nop 1\n\t"
+        "v_max_f32_dpp %0, %0, %0 quad_perm:[2,3,0,1] row_mask:0xf bank_mask:0xf\n\t"
+        "s_nop 1\n\t"
+        "v_max_f32_dpp %0, %0, %0 row_half_mirror row_mask:0xf bank_mask:0xf\n\t"
+        "s_nop 1\n\t"
+        "v_max_f32_dpp %0, %0, %0 row_mirror row_mask:0xf bank_mask:0xf\n\t"
+        "s_nop 1\n\t"
+        "v_max_f32_dpp %0, %0, %0 row_bcast:15 row_mask:0xa bank_mask:0xf\n\t"
+        "s_nop 1\n\t"
+        "v_max_f32_dpp %0, %0, %0 row_bcast:31 row_mask:0xc bank_mask:0xf\n\t"
+        "s_nop 1"
+        : "+v"(v));
     return last_lane(v);
 }
 
@@ -289,7 +299,7 @@ __device__ __forceinline__ void new_maximum(LaneState& s, float z[8], float chun
     new_rc = uniform_f(new_rc);
     if (s.rc > -INFINITY) {
         const float d = new_rc - s.rc;
-        const float f = exp2f(-d);
+        const float f = __builtin_amdgcn_exp2f(-d);           // exact: d is an integer
         s.W = fmaf(-d, s.S, s.W) * f;       s.S *= f;
         s.wT0 = fmaf(-d, s.sT0, s.wT0) * f; s.sT0 *= f;
         s.wT1 = fmaf(-d, s.sT1, s.wT1) * f; s.sT1 *= f;
@@ -306,14 +316,12 @@ __device__ __forceinline__ void new_maximum(LaneState& s, float z[8], float chun
     const unsigned long long holders = __ballot(chunk_max == top);
     s.dom_lane = __builtin_amdgcn_readfirstlane((int)__builtin_ctzll(holders | (1ull << 63)));
     s.dom_open = true;
-    if (lane == s.dom_lane) {
-        int hit = 8;
+    bool done = lane != s.dom_lane;
 #pragma unroll
-        for (int j = 7; j >= 0; --j)
-            if (z[j] == top) hit = j;                           // ends on the lowest such j
-#pragma unroll
-        for (int j = 0; j < 8; ++j)
-            if (j == hit) z[j] = kAbsent;
+    for (int j = 0; j < 8; ++j) {                               // strikes the lowest such j only
+        const bool hit = !done && z[j] == top;
+        z[j] = hit ? kAbsent : z[j];
+        done = done || hit;
     }
 }
 
@@ -323,7 +331,7 @@ __device__ __forceinline__ void accumulate_chunk(LaneState& s, float z[8], float
     const float cm = fmax3(fmax3(z[0], z[1], z[2]), fmax3(z[3], z[4], z[5]), fmax3(z[6], z[7], z[7]));
     // t_max > 0: the reference no longer covers this sweep (always so while rc = -inf)
     const float tmax = fmaf(cm, c, -s.rc);
-    if (__any(tmax > 0.0f)) new_maximum(s, z, cm, c, lane);
+    if (__builtin_expect(__any(tmax > 0.0f), 0)) new_maximum(s, z, cm, c, lane);
     const float nrc = -s.rc;
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
@@ -400,11 +408,13 @@ void vocab_pass_kernel(VocabPassArgs a)
     const uint32_t seed_lo = (uint32_t)a.seed, seed_hi = (uint32_t)(a.seed >> 32);
 
     // Training side: the target's logit is requested now and used in the epilogue.
+    // (Read from a clamped column without a branch, so that nothing waits on it here.)
     int64_t tgt = -1;
     float z_tgt = 0.0f;
-    if (!kSample && wave == 0 && a.target_ids != nullptr) {
-        tgt = a.target_ids[row];
-        if (tgt >= 0 && tgt < V) z_tgt = Chunk::load_one(rowp, tgt);
+    if (!kSample) {
+        if (a.target_ids != nullptr) tgt = a.target_ids[row];
+        const int64_t safe = tgt < 0 ? 0 : (tgt >= V ? V - 1 : tgt);
+        z_tgt = Chunk::load_one(rowp, safe);
     }
 
     LaneState s;
