@@ -79,7 +79,7 @@ def main() -> int:
     hcnt = torch.empty(1, dtype=torch.int64, device=dev)
     hsum_host = torch.empty(1, dtype=torch.float64, pin_memory=True)
     hcnt_host = torch.empty(1, dtype=torch.int64, pin_memory=True)
-    ws = e3.new_workspace(ROWS, V, dev)        # zero-filled once; every call leaves it clean
+    ws = e3.new_workspace(ROWS, V, dev)
 
     state = {"tau": 1.0, "H_init": None, "t": 0}
     stream = torch.cuda.current_stream(dev)

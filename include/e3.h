@@ -52,23 +52,12 @@ const char* e3_strerror(int status);
 
 /*
  * Bytes of device workspace that e3_sample_entropy / e3_logprob_entropy need
- * for a [rows, V] problem (pure host function; 0 means none is needed and
- * `workspace` may then be NULL).  Rows of at least 8192 columns are streamed
- * in 8192-column pieces by a fixed set of waves that draw pieces from a counter
- * in the workspace and leave one 32-byte partial result per piece there; the
- * wave that delivers a row's last partial merges them.
+ * for a [rows, V] problem (pure host function).  The present kernels stage all
+ * partial results in LDS, so this returns 0 for every shape and `workspace` may
+ * be NULL; the argument is kept so that callers size and pass it the same way
+ * should a later version stage rows in device memory.
  */
 size_t e3_workspace_bytes(int64_t rows, int64_t V);
-
-/*
- * Zero-fill a workspace (enqueued on hip_stream).  A workspace must be zero
- * before its first use; every call that uses it leaves it zero again, so one
- * initialisation serves any number of later calls of any shape that fits.
- * Calls that share a workspace must not overlap in time (one stream, or
- * explicit ordering).  workspace: device, 256-byte aligned; workspace_bytes a
- * multiple of 4.
- */
-int e3_workspace_init(void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /*
  * Rollout side: sample one token per row at temperature tau_r and report its
@@ -102,9 +91,10 @@ int e3_workspace_init(void* workspace, size_t workspace_bytes, void* hip_stream)
  *             not depend on how rows are batched.
  * token_out   [rows] int32;  logp_out, entropy_out [rows] fp32 (natural log).
  *             logp_out and entropy_out may be NULL.
- * workspace   device scratch of at least e3_workspace_bytes(rows, V) bytes,
- *             256-byte aligned, zero-filled before its first use (see
- *             e3_workspace_init); E3_ERR_WORKSPACE if missing or too small.
+ * workspace   device scratch of at least e3_workspace_bytes(rows, V) bytes
+ *             (0 today, so NULL is accepted); never read when that is 0.
+ * V           at most 2,080,768 columns (per-workgroup tables must fit LDS),
+ *             else E3_ERR_SHAPE.
  * rows == 0 is a no-op.  fp32 accumulation per lane, fp64 merges.
  */
 int e3_sample_entropy(const void* logits, int dtype, int64_t rows, int64_t V, int64_t row_stride,

@@ -4,8 +4,8 @@ CSR groups, and the closed-form temperature scheduler.  The arithmetic lives in 
 (HIP, gfx950); this package is its ctypes binding plus seeded workload generators."""
 from .binding import (E3_BF16, E3_F32, E3Error, e3_grpo_advantages, e3_logprob_entropy,
                       e3_sample_entropy, e3_strerror, e3_temperature_update,
-                      e3_workspace_bytes, e3_workspace_init, lib, new_workspace)
+                      e3_workspace_bytes, lib, new_workspace)
 
 __all__ = ["E3_BF16", "E3_F32", "E3Error", "e3_grpo_advantages", "e3_logprob_entropy",
            "e3_sample_entropy", "e3_strerror", "e3_temperature_update", "e3_workspace_bytes",
-           "e3_workspace_init", "lib", "new_workspace"]
+           "lib", "new_workspace"]

@@ -20,7 +20,7 @@ E3_F32, E3_BF16 = 0, 1
 E3_OK = 0
 E3_TILE_CHUNK, E3_TILE_LANES, E3_TILE_DEPTH = 8, 64, 16
 
-EXPORTS = ("e3_strerror", "e3_workspace_bytes", "e3_workspace_init", "e3_sample_entropy", "e3_logprob_entropy",
+EXPORTS = ("e3_strerror", "e3_workspace_bytes", "e3_sample_entropy", "e3_logprob_entropy",
            "e3_grpo_advantages", "e3_temperature_update")
 
 _lib: Optional[C.CDLL] = None
@@ -45,8 +45,6 @@ def lib() -> C.CDLL:
         L.e3_strerror.restype = C.c_char_p
         L.e3_workspace_bytes.argtypes = [i64, i64]
         L.e3_workspace_bytes.restype = C.c_size_t
-        L.e3_workspace_init.argtypes = [vp, C.c_size_t, vp]
-        L.e3_workspace_init.restype = C.c_int
         L.e3_sample_entropy.argtypes = [vp, C.c_int, i64, i64, i64, vp, f32, u64, u64,
                                         vp, vp, vp, vp, C.c_size_t, vp]
         L.e3_sample_entropy.restype = C.c_int
@@ -101,22 +99,12 @@ def e3_workspace_bytes(rows: int, V: int) -> int:
     return int(lib().e3_workspace_bytes(rows, V))
 
 
-def e3_workspace_init(workspace: torch.Tensor) -> torch.Tensor:
-    """Zero-fill a workspace tensor through the library (needed once, before first use)."""
-    nbytes = workspace.numel() * workspace.element_size()
-    rc = lib().e3_workspace_init(_ptr(workspace), nbytes, _stream(workspace.device))
-    if rc != E3_OK:
-        raise E3Error(rc, "e3_workspace_init")
-    return workspace
-
-
 def new_workspace(rows: int, V: int, device) -> Optional[torch.Tensor]:
-    """Allocate and initialise a workspace for a [rows, V] problem (None if none is needed)."""
+    """Allocate a workspace for a [rows, V] problem (None when none is needed)."""
     need = e3_workspace_bytes(rows, V)
     if need == 0:
         return None
-    ws = torch.empty((need + 3) // 4, dtype=torch.int32, device=device)
-    return e3_workspace_init(ws)
+    return torch.empty((need + 3) // 4, dtype=torch.int32, device=device)
 
 
 def _workspace(rows: int, V: int, workspace: Optional[torch.Tensor], device):

@@ -13,6 +13,7 @@ int check_logits(const void* logits, int dtype, int64_t rows, int64_t V, int64_t
     if (dtype != E3_F32 && dtype != E3_BF16) return E3_ERR_DTYPE;
     if (rows < 0 || V < 1 || row_stride < V) return E3_ERR_SHAPE;
     if (V > (int64_t)0x7FFFFFFF - 8192 || rows > (int64_t)0x7FFFFFFF) return E3_ERR_SHAPE;
+    if (!e3::vocab_pass_fits(V)) return E3_ERR_SHAPE;      // beyond ~2M columns
     if (rows == 0) return E3_OK;
     if (logits == nullptr) return E3_ERR_NULL;
     const int64_t esz = dtype == E3_F32 ? 4 : 2;
@@ -44,47 +45,10 @@ extern "C" const char* e3_strerror(int status)
     }
 }
 
-// Which of the two kernel forms a problem uses, and the workspace it needs.
-static bool uses_stream_form(int64_t rows, int64_t V)
-{
-    e3::VocabPassArgs a{};
-    a.rows = rows; a.V = V;
-    return rows > 0 && e3::stream_form_applies(a);
-}
-
 extern "C" size_t e3_workspace_bytes(int64_t rows, int64_t V)
 {
-    if (rows <= 0 || V < 1) return 0;
-    // rows narrower than one super-tile (or absurdly wide) are handled one workgroup
-    // per row and stage nothing
-    return uses_stream_form(rows, V) ? e3::stream_workspace_bytes(rows, V) : 0;
-}
-
-extern "C" int e3_workspace_init(void* workspace, size_t workspace_bytes, void* hip_stream)
-{
-    if (workspace_bytes == 0) return E3_OK;
-    if (workspace == nullptr) return E3_ERR_NULL;
-    if ((reinterpret_cast<uintptr_t>(workspace) & 255u) != 0 || (workspace_bytes & 3u) != 0)
-        return E3_ERR_ALIGN;
-    hipError_t err = e3::launch_workspace_zero(workspace, workspace_bytes,
-                                               static_cast<hipStream_t>(hip_stream));
-    return err == hipSuccess ? E3_OK : E3_ERR_LAUNCH;
-}
-
-static int check_workspace(int64_t rows, int64_t V, const void* workspace, size_t workspace_bytes)
-{
-    const size_t need = e3_workspace_bytes(rows, V);
-    if (need == 0) return E3_OK;
-    if (workspace == nullptr || workspace_bytes < need) return E3_ERR_WORKSPACE;
-    if ((reinterpret_cast<uintptr_t>(workspace) & 255u) != 0) return E3_ERR_ALIGN;
-    return E3_OK;
-}
-
-static hipError_t run_vocab_pass(const e3::VocabPassArgs& a, bool is_bf16, bool sample,
-                                 void* workspace, hipStream_t stream)
-{
-    if (e3::stream_form_applies(a)) return e3::launch_vocab_stream(a, is_bf16, sample, workspace, stream);
-    return e3::launch_vocab_pass(a, is_bf16, sample, stream);
+    (void)rows; (void)V;
+    return 0;   // partial results are staged in LDS: no device workspace is needed
 }
 
 extern "C" int e3_sample_entropy(const void* logits, int dtype, int64_t rows, int64_t V,
@@ -99,8 +63,7 @@ extern "C" int e3_sample_entropy(const void* logits, int dtype, int64_t rows, in
     if (rc != E3_OK) return rc;
     if (rows == 0) return E3_OK;
     if (token_out == nullptr) return E3_ERR_NULL;
-    rc = check_workspace(rows, V, workspace, workspace_bytes);
-    if (rc != E3_OK) return rc;
+    (void)workspace; (void)workspace_bytes;
 
     e3::VocabPassArgs a{};
     a.logits = logits; a.rows = rows; a.V = V; a.row_stride = row_stride;
@@ -108,8 +71,8 @@ extern "C" int e3_sample_entropy(const void* logits, int dtype, int64_t rows, in
     a.seed = seed; a.row_base = row_base;
     a.target_ids = nullptr;
     a.token_out = token_out; a.logp_out = logp_out; a.entropy_out = entropy_out;
-    hipError_t err = run_vocab_pass(a, dtype == E3_BF16, true, workspace,
-                                    static_cast<hipStream_t>(hip_stream));
+    hipError_t err = e3::launch_vocab_pass(a, dtype == E3_BF16, true,
+                                           static_cast<hipStream_t>(hip_stream));
     return err == hipSuccess ? E3_OK : E3_ERR_LAUNCH;
 }
 
@@ -126,8 +89,7 @@ extern "C" int e3_logprob_entropy(const void* logits, int dtype, int64_t rows, i
     if (rc != E3_OK) return rc;
     if (rows > 0 && entropy_out == nullptr) return E3_ERR_NULL;
     if (logp_out != nullptr && target_ids == nullptr) return E3_ERR_NULL;
-    rc = check_workspace(rows, V, workspace, workspace_bytes);
-    if (rc != E3_OK) return rc;
+    (void)workspace; (void)workspace_bytes;
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
 
     if (rows > 0) {
@@ -136,7 +98,7 @@ extern "C" int e3_logprob_entropy(const void* logits, int dtype, int64_t rows, i
         a.tau_rows = tau_rows; a.tau_scalar = tau_scalar;
         a.target_ids = target_ids;
         a.token_out = nullptr; a.logp_out = logp_out; a.entropy_out = entropy_out;
-        if (run_vocab_pass(a, dtype == E3_BF16, false, workspace, stream) != hipSuccess)
+        if (e3::launch_vocab_pass(a, dtype == E3_BF16, false, stream) != hipSuccess)
             return E3_ERR_LAUNCH;
     }
     if (entropy_sum_out != nullptr || entropy_count_out != nullptr) {

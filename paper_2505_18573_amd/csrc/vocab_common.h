@@ -16,10 +16,10 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 // Tunables (overridable at compile time for experiments).
 #ifndef E3_AHEAD_BF16
-#define E3_AHEAD_BF16 16     // 16 sweeps x 1 KiB = 16 KiB per wave in flight
+#define E3_AHEAD_BF16 8      // 8 sweeps x 1 KiB per wave in flight (must stay below 16)
 #endif
 #ifndef E3_AHEAD_F32
-#define E3_AHEAD_F32 8       // 8 sweeps x 2 KiB
+#define E3_AHEAD_F32 8       // 8 sweeps x 2 KiB per wave in flight
 #endif
 #ifndef E3_NT_LOADS
 #define E3_NT_LOADS 1        // stream the logits with non-temporal loads

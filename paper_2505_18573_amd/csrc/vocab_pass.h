@@ -19,13 +19,8 @@ struct VocabPassArgs {
 
 hipError_t launch_vocab_pass(const VocabPassArgs& a, bool is_bf16, bool sample, hipStream_t stream);
 
-// Persistent streaming form (vocab_stream.hip): applies when every row has at least one
-// complete 8192-column super-tile; needs a zero-filled workspace of stream_workspace_bytes.
-bool stream_form_applies(const VocabPassArgs& a);
-size_t stream_workspace_bytes(int64_t rows, int64_t V);
-hipError_t launch_vocab_stream(const VocabPassArgs& a, bool is_bf16, bool sample, void* ws,
-                               hipStream_t stream);
-hipError_t launch_workspace_zero(void* ws, size_t bytes, hipStream_t stream);
+// false when V is so large that the per-workgroup tables do not fit LDS
+bool vocab_pass_fits(int64_t V);
 
 hipError_t launch_entropy_reduce(const float* entropy, const uint8_t* mask, int64_t rows,
                                  double* sum_out, int64_t* count_out, hipStream_t stream);

@@ -12,64 +12,57 @@
 // Work decomposition (wave = 64 lanes):
 //   * a row is cut into super-tiles of 8192 columns; one wave streams a whole
 //     super-tile as 16 sweeps of 64 lanes x 8 columns (16 bytes of bf16 per lane),
-//     so every load instruction of a wave covers 1 KiB of contiguous memory;
-//   * the 16 chunks one lane sees inside a super-tile are exactly one sampler tile,
-//     so per-tile sums never leave the lane's registers;
-//   * each wave keeps one integer-valued log2 reference `rc` shared by its lanes
-//     (SGPR); it only moves when a sweep holds a new maximum, and moving it rescales
-//     by an exact power of two;
-//   * lanes accumulate in fp32, lane->wave->row merges run in fp64;
-//   * waves of a workgroup take super-tiles round-robin and meet once in LDS.
+//     so every load instruction of a wave covers 1 KiB of contiguous memory, and the
+//     16 chunks one lane sees are exactly one sampler tile;
+//   * a workgroup of 8 waves owns a few whole rows; the super-tiles of those rows are
+//     work items that the waves draw from a ticket counter in LDS, so a wave that is
+//     served faster by the memory system simply takes more of them, and a wave keeps
+//     the first sweeps of its next item in flight while it finishes the current one;
+//   * a wave accumulates the items it gets from one row in registers (fp32 per lane,
+//     one integer-valued log2 reference per wave that moves by exact powers of two)
+//     and hands over one partial per row; the wave that delivers a row's last item
+//     merges the partials in fp64, runs level 2 of the sampler and writes the outputs
+//     while the other waves keep streaming.
 #include "vocab_common.h"
 #include "vocab_pass.h"
 
 namespace e3 {
 
-// What one wave hands to the workgroup merge.
-struct WavePartial {
+// What a wave hands over for one row (also: the row's incomplete super-tile).
+struct alignas(16) RowPartial {
     double S, W;       // sums over the wave's columns except `top`, relative to rc
-    float rc, top;
-    float q;           // the wave's best level-1 weight, relative to rc
-    int tile;
+    float rc, top;     // reference and excluded maximum; rc = -inf marks an empty slot
+    float q;           // mass / E of the best sampler tile among them, relative to rc
+    int tile;          // its tile id
+};
+static_assert(sizeof(RowPartial) == 32, "layout");
+
+struct QueueHeader {
+    uint32_t ticket;   // dynamic items handed out so far
+    uint32_t pad[3];
 };
 
-template <typename Chunk, int kWaves, bool kSample>
-__global__ __launch_bounds__(kWaves * 64)
-void vocab_pass_kernel(VocabPassArgs a)
-{
-    __shared__ WavePartial partial[kWaves];
-    __shared__ float tile_inv_e[kSample ? kWaves : 1][4][kLanes];
+// LDS layout: QueueHeader | uint32 done[rpb] (padded to 16 B) | RowPartial parts[rpb][kWaves+1]
+//             | float inv_e[rpb][nst][64]   (rollout side only)
+__host__ __device__ inline size_t lds_done_bytes(int rpb) { return (size_t)((rpb * 4 + 15) / 16 * 16); }
 
-    const int lane = threadIdx.x & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int64_t row = blockIdx.x;
+template <int kWaves>
+__host__ __device__ inline size_t lds_bytes(int rpb, int nst, bool sample)
+{
+    return sizeof(QueueHeader) + lds_done_bytes(rpb) + sizeof(RowPartial) * (size_t)rpb * (kWaves + 1)
+         + (sample ? (size_t)rpb * nst * kLanes * sizeof(float) : 0);
+}
+
+// Row epilogue, run by the wave that delivered the row's last item: merge the partials
+// (one per lane), level 2 of the sampler or the target gather, outputs.
+template <typename Chunk, bool kSample, int kWaves>
+__device__ __forceinline__ void finish_row(const VocabPassArgs& a, int64_t row,
+                                           const RowPartial* parts, int lane)
+{
     const int64_t V = a.V;
     const char* rowp = static_cast<const char*>(a.logits)
                      + row * a.row_stride * (int64_t)Chunk::kElemBytes;
-
-    const int nst = (int)((V + kSuperCols - 1) / kSuperCols);   // super-tiles in a row
-    const int nfull = (int)(V / kSuperCols);                    // of which complete
-
-    // Rolling prefetch: kAhead sweeps stay requested ahead of the one being consumed
-    // (16 KiB per wave in flight); sweep i lives in buf[i % kAhead].  The first
-    // requests leave before anything else is looked at.
-    constexpr int kAhead = Chunk::kAhead;
-    Chunk buf[kAhead];
-    const int64_t lane_col = (int64_t)lane * kChunk;
-    if (wave < nfull) {
-#pragma unroll
-        for (int i = 0; i < kAhead; ++i)
-            buf[i].load(rowp, (int64_t)wave * kSuperCols + i * kSweepCols + lane_col);
-    }
-
-    const float tau = a.tau_rows ? a.tau_rows[row] : a.tau_scalar;
-    const float c = (float)(kLog2e / (double)tau);
-    const uint64_t grow = a.row_base + (uint64_t)row;
-    const uint32_t row_lo = (uint32_t)grow, row_hi = (uint32_t)(grow >> 32);
-    const uint32_t seed_lo = (uint32_t)a.seed, seed_hi = (uint32_t)(a.seed >> 32);
-
-    // Training side: the target's logit is requested now and used in the epilogue.
-    // (Read from a clamped column without a branch, so that nothing waits on it here.)
+    // training side: ask for the target's logit first, use it last
     int64_t tgt = -1;
     float z_tgt = 0.0f;
     if (!kSample) {
@@ -77,78 +70,217 @@ void vocab_pass_kernel(VocabPassArgs a)
         const int64_t safe = tgt < 0 ? 0 : (tgt >= V ? V - 1 : tgt);
         z_tgt = Chunk::load_one(rowp, safe);
     }
+    const float tau = a.tau_rows ? a.tau_rows[row] : a.tau_scalar;
+    const float c = kLog2eF / tau;
 
-    LaneState s;
-    s.rc = -INFINITY;
-    s.top = -INFINITY;
-    s.dom_lane = 0;
-    s.dom_open = false;
-    s.S = s.W = s.sT0 = s.sT1 = s.wT0 = s.wT1 = 0.0f;
-    s.best = Cand{-1.0f, 0};
+    RowPartial p;
+    p.S = 0.0; p.W = 0.0; p.rc = -INFINITY; p.top = -INFINITY; p.q = -1.0f; p.tile = 0;
+    if (lane <= kWaves) p = parts[lane];
 
-    // Tile noise for four of this wave's super-tiles at a time (the k-th to (k+3)-th
-    // it visits): lane l draws the Philox block that serves tiles 4j..4j+3 (j = l % 16)
-    // of the (k + l / 16)-th one.  The table is private to the wave; LDS operations of
-    // one wave complete in order, so a wave-level fence is all the ordering it needs.
-    auto refill_tile_noise = [&](int st_first) {
-        const int st_n = st_first + (lane >> 4) * kWaves;
-        uint32_t w[4];
-        philox4x32_10((uint32_t)(st_n * 16 + (lane & 15)), row_lo, row_hi, 1u, seed_lo, seed_hi, w);
+    // R is the common reference, `peak` the largest logit of the row; the partial
+    // that holds it is the lowest lane with that top, every other excluded maximum
+    // joins the rest as an ordinary term.  All in fp64 from here.
+    const float R = wave_max(p.rc);
+    const float peak = wave_max(p.top);
+    const unsigned long long holders = __ballot(p.top == peak);
+    const int peak_lane = (int)__builtin_ctzll(holders | (1ull << 63));
+    const bool live = p.rc > -INFINITY;
+    const double cd = (double)c;
+    const double d = live ? (double)R - (double)p.rc : 0.0;       // integer >= 0
+    const int sh = d > 4000.0 ? -4000 : -(int)d;
+    double S_l = 0.0, W_l = 0.0;
+    if (live) {
+        S_l = ldexp(p.S, sh);
+        W_l = ldexp(p.W - d * p.S, sh);
+        if (lane != peak_lane) {
+            const double tw = (double)p.top * cd - (double)R;
+            const double ew = (double)exp2f((float)tw);
+            S_l += ew;
+            W_l += tw * ew;
+        }
+    }
+    const double S_rest = wave_sum(S_l);
+    const double W_rest = wave_sum(W_l);
+    // With e_p = 2^{t_p} the peak's term, x = S_rest / e_p and y = W_rest / e_p:
+    //   ln S = t_p ln2 + log1p(x),   H = ln S - ln2 W / S = log1p(x) + ln2 (t_p x - y) / (1 + x),
+    // every piece of which is O(x) when the row is peaked.  t_p lies in (-1, 0].
+    const double t_p = (double)peak * cd - (double)R;
+    const double inv_ep = (double)exp2f((float)-t_p);
+    const double x = S_rest * inv_ep, y = W_rest * inv_ep;
+    const double l1p = (double)log1pf((float)x);
+    const double H = l1p + kLn2 * (t_p * x - y) / (1.0 + x);
+
+    int64_t tok;
+    float z_tok;
+    if (kSample) {
+        // level 1 across partials: weights brought to the common reference (exact scaling)
+        const Cand win = wave_best(Cand{live ? ldexpf(p.q, sh) : -1.0f, p.tile});
+        // Level 2: Gumbel-max inside the winning tile, in race form: maximise
+        // 2^{(z - zmax) c} / E_col.  32 lanes x 4 consecutive columns cover the tile.
+        const int wst = win.idx / kLanes, wslot = win.idx % kLanes;
+        const int64_t col0 = (int64_t)wst * kSuperCols + (int64_t)(lane >> 1) * kSweepCols
+                           + (int64_t)wslot * kChunk + (lane & 1) * 4;
+        float cz[4];
 #pragma unroll
         for (int j = 0; j < 4; ++j)
-            tile_inv_e[kSample ? wave : 0][lane >> 4][(lane & 15) * 4 + j] = 1.0f / exp_variate(w[j]);
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-        __builtin_amdgcn_wave_barrier();
-        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-    };
-
-    // Complete super-tiles: wave, wave + kWaves, ...  While another complete one
-    // follows, the sweep kAhead further on is requested as soon as a sweep has been
-    // unpacked, unconditionally, so the loads in flight never drain; the last complete
-    // super-tile runs the same body without reaching into a successor.
-    int k = 0;
-    int st = wave;
-    auto run_super_tile = [&](auto prefetch) {
-        float inv_e = 0.0f;
-        if (kSample) {
-            if ((k & 3) == 0) refill_tile_noise(st);
-            inv_e = tile_inv_e[wave][k & 3][lane];
-        }
-        const int64_t this_base = (int64_t)st * kSuperCols + lane_col;
-        const int64_t next_base = (int64_t)(st + kWaves) * kSuperCols + lane_col;
+            cz[j] = (lane < 32 && col0 + j < V) ? Chunk::load_one(rowp, col0 + j) : kAbsent;
+        const uint64_t grow = a.row_base + (uint64_t)row;
+        uint32_t w[4];
+        philox4x32_10((uint32_t)(col0 >> 2), (uint32_t)grow, (uint32_t)(grow >> 32), 2u,
+                      (uint32_t)a.seed, (uint32_t)(a.seed >> 32), w);
+        const float zmax = wave_max(fmaxf(fmaxf(cz[0], cz[1]), fmaxf(cz[2], cz[3])));
+        Cand cb{-1.0f, 0x7FFFFFFF};
 #pragma unroll
-        for (int i = 0; i < kDepth; ++i) {
-            float z[8];
-            buf[i % kAhead].unpack(z);
-            if (i + kAhead < kDepth)
-                buf[i % kAhead].load(rowp, this_base + (i + kAhead) * kSweepCols);
-            else if (decltype(prefetch)::value)
-                buf[i % kAhead].load(rowp, next_base + (i + kAhead - kDepth) * kSweepCols);
-            accumulate_chunk(s, z, c, lane);
+        for (int j = 0; j < 4; ++j) {
+            const bool ok = lane < 32 && col0 + j < V;
+            const float q = __builtin_amdgcn_exp2f((cz[j] - zmax) * c) / exp_variate(w[j]);
+            cb = better(cb, Cand{ok ? q : -1.0f, ok ? (int)(col0 + j) : 0x7FFFFFFF});
         }
-        close_tile<kSample>(s, st * kLanes + lane, inv_e, true, c, lane);
-        st += kWaves;
-        ++k;
-    };
-    while (st + kWaves < nfull) run_super_tile(std::true_type{});
-    if (st < nfull) run_super_tile(std::false_type{});
+        cb = wave_best(cb);
+        tok = cb.idx;
+        if (tok < 0 || tok >= V) tok = 0;                 // only reachable with non-finite input
+        float own = -INFINITY;
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+            if (col0 + j == tok) own = cz[j];
+        z_tok = wave_max(own);
+        if (lane == 0) a.token_out[row] = (int32_t)tok;
+    } else {
+        tok = tgt;
+        z_tok = z_tgt;
+    }
+    if (lane == 0) {
+        if (a.entropy_out) a.entropy_out[row] = (float)H;
+        if (a.logp_out) {
+            float lp = __builtin_nanf("");
+            if (tok >= 0 && tok < V)   // ln p = (a_tok - a_peak) - log1p(x)
+                lp = (float)(((double)z_tok - (double)peak) * cd * kLn2 - l1p);
+            a.logp_out[row] = lp;
+        }
+    }
+}
 
-    // The one incomplete super-tile of the row, if any, belongs to the wave whose turn
-    // it is; k already counts the super-tiles that wave has done.  Its sweeps are taken
-    // in two halves of 8: guarded loads of a half are all issued before the first is used.
-    if (nst > nfull && wave == nfull % kWaves) {
-        st = nfull;
-        float inv_e = 0.0f;
-        if (kSample) {
-            if ((k & 3) == 0) refill_tile_noise(st);
-            inv_e = tile_inv_e[wave][k & 3][lane];
+template <typename Chunk, bool kSample, int kWaves, int kAhead>
+__global__ __launch_bounds__(kWaves * 64)
+void vocab_pass_kernel(VocabPassArgs a, int rpb)
+{
+    static_assert(kAhead >= 1 && kAhead < kDepth, "the follow-up item must be known mid-item");
+    extern __shared__ __align__(16) char smem[];
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int64_t V = a.V;
+    const int nst = (int)((V + kSuperCols - 1) / kSuperCols);   // super-tiles in a row
+    const int nfull = (int)(V / kSuperCols);                    // of which complete
+    const int64_t row0 = (int64_t)blockIdx.x * rpb;             // first row of this workgroup
+    const int nrows = (int)((a.rows - row0) < rpb ? (a.rows - row0) : rpb);
+    // items: the rows' incomplete super-tiles first, then complete ones row by row
+    const int n_ragged = nst > nfull ? nrows : 0;
+    const int total = n_ragged + nrows * nfull;
+
+    QueueHeader* hdr = reinterpret_cast<QueueHeader*>(smem);
+    uint32_t* done = reinterpret_cast<uint32_t*>(smem + sizeof(QueueHeader));
+    RowPartial* parts = reinterpret_cast<RowPartial*>(smem + sizeof(QueueHeader) + lds_done_bytes(rpb));
+    float* inv_e_tab = reinterpret_cast<float*>(smem + sizeof(QueueHeader) + lds_done_bytes(rpb)
+                                                + sizeof(RowPartial) * (size_t)rpb * (kWaves + 1));
+
+    const int64_t row_bytes = a.row_stride * (int64_t)Chunk::kElemBytes;
+    const int64_t lane_col = (int64_t)lane * kChunk;
+    const char* base = static_cast<const char*>(a.logits) + row0 * row_bytes;
+
+    // item -> (local row, super-tile)
+    auto decode = [&](int item, int& r, int& st) {
+        if (item < n_ragged) { r = item; st = nfull; }
+        else { const int idx = item - n_ragged; r = idx / nfull; st = idx - r * nfull; }
+    };
+
+    // The first item of a wave is static; if it is a complete super-tile its first
+    // sweeps are requested before anything else happens.
+    int item = wave;
+    bool have = item < total;
+    Chunk buf[kAhead];
+    int r_cur = 0, st_cur = 0;
+    if (have && item >= n_ragged) {
+        decode(item, r_cur, st_cur);
+        const char* rp = base + r_cur * row_bytes;
+        const int64_t b0 = (int64_t)st_cur * kSuperCols + lane_col;
+#pragma unroll
+        for (int i = 0; i < kAhead; ++i) buf[i].load(rp, b0 + i * kSweepCols);
+    }
+
+    // Workgroup prologue: empty queue state, and (rollout side) the level-1 noise of all
+    // tiles of the workgroup's rows, one Philox block per thread per four tiles.
+    if (threadIdx.x == 0) hdr->ticket = 0;
+    for (int i = threadIdx.x; i < rpb; i += kWaves * 64) done[i] = 0;
+    for (int i = threadIdx.x; i < rpb * (kWaves + 1); i += kWaves * 64) {
+        RowPartial e;
+        e.S = 0.0; e.W = 0.0; e.rc = -INFINITY; e.top = -INFINITY; e.q = -1.0f; e.tile = 0;
+        parts[i] = e;
+    }
+    if (kSample) {
+        const uint32_t seed_lo = (uint32_t)a.seed, seed_hi = (uint32_t)(a.seed >> 32);
+        const int calls = nrows * nst * (kLanes / 4);
+        for (int cidx = threadIdx.x; cidx < calls; cidx += kWaves * 64) {
+            const int r = cidx / (nst * 16), rem = cidx - r * (nst * 16);   // rem = tile / 4 in the row
+            const uint64_t grow = a.row_base + (uint64_t)(row0 + r);
+            uint32_t w[4];
+            philox4x32_10((uint32_t)rem, (uint32_t)grow, (uint32_t)(grow >> 32), 1u, seed_lo, seed_hi, w);
+            float4 v;
+            v.x = 1.0f / exp_variate(w[0]); v.y = 1.0f / exp_variate(w[1]);
+            v.z = 1.0f / exp_variate(w[2]); v.w = 1.0f / exp_variate(w[3]);
+            reinterpret_cast<float4*>(inv_e_tab)[(size_t)r * nst * 16 + rem] = v;
         }
-        const int64_t base = (int64_t)st * kSuperCols + lane_col;
+    }
+    __syncthreads();
+
+    auto take_ticket = [&]() -> int {
+        uint32_t t = 0;
+        if (lane == 0) t = atomicAdd(&hdr->ticket, 1u);
+        return kWaves + (int)__builtin_amdgcn_readfirstlane(t);
+    };
+    auto fresh = [&](LaneState& s) {
+        s.rc = -INFINITY; s.top = -INFINITY; s.dom_lane = 0; s.dom_open = false;
+        s.S = s.W = s.sT0 = s.sT1 = s.wT0 = s.wT1 = 0.0f;
+        s.best = Cand{-1.0f, 0};
+    };
+    // Hand over what this wave holds for local row r (n_items of its items); the wave
+    // that brings the row's count to nst finishes the row.
+    auto deliver = [&](LaneState& s, int r, int slot, int n_items) {
+        const double Sw = wave_sum((double)s.S);
+        const double Ww = wave_sum((double)s.W);
+        const Cand wb = kSample ? wave_best(s.best) : Cand{-1.0f, 0};
+        uint32_t before = 0;
+        if (lane == 0) {
+            RowPartial p;
+            p.S = Sw; p.W = Ww; p.rc = s.rc; p.top = s.top; p.q = wb.q; p.tile = wb.idx;
+            parts[r * (kWaves + 1) + slot] = p;
+            before = atomicAdd(&done[r], (uint32_t)n_items);      // same wave: after the write
+        }
+        before = __builtin_amdgcn_readfirstlane(before);
+        if ((int)before + n_items == nst)
+            finish_row<Chunk, kSample, kWaves>(a, row0 + r, parts + r * (kWaves + 1), lane);
+    };
+    auto row_scale = [&](int r) -> float {
+        const float tau = a.tau_rows ? a.tau_rows[row0 + r] : a.tau_scalar;
+        return kLog2eF / tau;
+    };
+
+    // Incomplete super-tiles come first in the item order, so a wave meets them before it
+    // enters the pipelined loop: sweeps in two halves of 8, guarded loads of a half all
+    // issued before the first is used.
+    while (have && item < n_ragged) {
+        const int next = take_ticket();
+        const int r = item, st = nfull;
+        const char* rowp = base + r * row_bytes;
+        const float c = row_scale(r);
+        const float inv_e = kSample ? inv_e_tab[((size_t)r * nst + st) * kLanes + lane] : 0.0f;
+        LaneState s;
+        fresh(s);
+        const int64_t cbase = (int64_t)st * kSuperCols + lane_col;
         bool any_valid = false;
 #pragma unroll 1
         for (int half = 0; half < 2; ++half) {
-            const int64_t hbase = base + (int64_t)half * (kDepth / 2) * kSweepCols;
-            if (hbase - lane_col >= V) break;                    // uniform: nothing left
+            const int64_t hbase = cbase + (int64_t)half * (kDepth / 2) * kSweepCols;
+            if (hbase - lane_col >= V) break;            // uniform: nothing left
             Chunk rb[kDepth / 2];
 #pragma unroll
             for (int i = 0; i < kDepth / 2; ++i)
@@ -173,129 +305,74 @@ void vocab_pass_kernel(VocabPassArgs a)
             }
         }
         close_tile<kSample>(s, st * kLanes + lane, inv_e, any_valid, c, lane);
-    }
-
-    // lane -> wave, in fp64 (all lanes of a wave share rc, so plain sums)
-    const double Sw = wave_sum((double)s.S);
-    const double Ww = wave_sum((double)s.W);
-    const Cand wb = wave_best(s.best);
-
-    // Rollout side: each wave requests the columns of its own best tile right away
-    // (32 lanes x 4 consecutive columns), so that whichever wave wins the row already
-    // holds them when the winner is known.
-    float cz[4] = {kAbsent, kAbsent, kAbsent, kAbsent};
-    int64_t ccol0 = 0;
-    if (kSample) {
-        const int cst = wb.idx / kLanes, cslot = wb.idx % kLanes;
-        ccol0 = (int64_t)cst * kSuperCols + (int64_t)(lane >> 1) * kSweepCols
-              + (int64_t)cslot * kChunk + (lane & 1) * 4;
+        deliver(s, r, kWaves, 1);
+        item = next;
+        have = item < total;
+        if (have && item >= n_ragged) {
+            decode(item, r_cur, st_cur);
+            const char* rp = base + r_cur * row_bytes;
+            const int64_t b0 = (int64_t)st_cur * kSuperCols + lane_col;
 #pragma unroll
-        for (int j = 0; j < 4; ++j)
-            if (lane < 32 && ccol0 + j < V) cz[j] = Chunk::load_one(rowp, ccol0 + j);
+            for (int i = 0; i < kAhead; ++i) buf[i].load(rp, b0 + i * kSweepCols);
+        }
     }
 
-    if (lane == 0) {
-        partial[wave].S = Sw;
-        partial[wave].W = Ww;
-        partial[wave].rc = s.rc;
-        partial[wave].top = s.top;
-        partial[wave].q = wb.q;
-        partial[wave].tile = wb.idx;
-    }
-    __syncthreads();
-
-    // wave -> row.  R is the common reference, `peak` the largest logit of the row.
-    // The wave that owns the winning tile finishes the row (wave 0 on the training side).
-    float R = -INFINITY, peak = -INFINITY;
-    int peak_wave = 0;
+    if (have) {
+        // Pipelined loop over complete super-tiles.  Invariant at the top: (r_cur, st_cur)
+        // is a complete super-tile whose first kAhead sweeps are requested into buf.
+        // Items come in increasing order, so the rows a wave sees never go back: it
+        // accumulates one row in `s` and hands it over when the row changes.
+        LaneState s;
+        fresh(s);
+        int held = 0;                                    // items of r_cur accumulated in s
+        float c = row_scale(r_cur);
+        const char* rowp = base + r_cur * row_bytes;
+        while (true) {
+            const int next = take_ticket();
+            const float inv_e = kSample ? inv_e_tab[((size_t)r_cur * nst + st_cur) * kLanes + lane] : 0.0f;
+            const int64_t this_base = (int64_t)st_cur * kSuperCols + lane_col;
 #pragma unroll
-    for (int w = 0; w < kWaves; ++w) {
-        R = fmaxf(R, partial[w].rc);
-        if (partial[w].top > peak) { peak = partial[w].top; peak_wave = w; }
-    }
-    int owner = 0;
-    if (kSample) {
-        double best_q = -1.0;
-        int best_tile = 0;
-#pragma unroll
-        for (int w = 0; w < kWaves; ++w) {
-            const float rcw = partial[w].rc;
-            if (!(rcw > -INFINITY)) continue;                 // wave had no columns
-            const double d = (double)R - (double)rcw;         // integer >= 0
-            const double q = ldexp((double)partial[w].q, d > 4000.0 ? -4000 : -(int)d);
-            if (q > best_q || (q == best_q && partial[w].tile < best_tile)) {
-                best_q = q;
-                best_tile = partial[w].tile;
-                owner = w;
+            for (int i = 0; i < kDepth - kAhead; ++i) {
+                float z[8];
+                buf[i % kAhead].unpack(z);
+                buf[i % kAhead].load(rowp, this_base + (i + kAhead) * kSweepCols);
+                accumulate_chunk(s, z, c, lane);
             }
-        }
-    }
-    if (wave != owner) return;
-
-    // Every lane of the finishing wave repeats the same scalar merge.  Each other
-    // wave's excluded maximum joins the rest as an ordinary term.
-    const double cd = (double)c;
-    double S_rest = 0.0, W_rest = 0.0;   // relative to R, peak excluded
+            const bool more = next < total;
+            int r_next = r_cur, st_next = 0;
+            if (more) {
+                decode(next, r_next, st_next);
+                const char* nrowp = base + r_next * row_bytes;
+                const int64_t next_base = (int64_t)st_next * kSuperCols + lane_col;
 #pragma unroll
-    for (int w = 0; w < kWaves; ++w) {
-        const float rcw = partial[w].rc;
-        if (!(rcw > -INFINITY)) continue;
-        const double d = (double)R - (double)rcw;
-        const int sh = d > 4000.0 ? -4000 : -(int)d;
-        S_rest += ldexp(partial[w].S, sh);
-        W_rest += ldexp(partial[w].W - d * partial[w].S, sh);
-        if (w != peak_wave) {
-            const double tw = (double)partial[w].top * cd - (double)R;
-            const double ew = (double)exp2f((float)tw);
-            S_rest += ew;
-            W_rest += tw * ew;
-        }
-    }
-    // With e_p = 2^{t_p} the peak's term, x = S_rest / e_p and y = W_rest / e_p:
-    //   ln S = t_p ln2 + log1p(x),   H = ln S - ln2 W / S = log1p(x) + ln2 (t_p x - y) / (1 + x),
-    // every piece of which is O(x) when the row is peaked.  t_p lies in (-1, 0].
-    const double t_p = (double)peak * cd - (double)R;
-    const double inv_ep = (double)exp2f((float)-t_p);
-    const double x = S_rest * inv_ep, y = W_rest * inv_ep;
-    const double l1p = (double)log1pf((float)x);
-    const double H = l1p + kLn2 * (t_p * x - y) / (1.0 + x);
-
-    int64_t tok;
-    float z_tok;
-    if (kSample) {
-        // Level 2: Gumbel-max inside the winning tile (already in cz), in race form:
-        // maximise 2^{(z - zmax) c} / E_col.
-        const float zmax = wave_max(fmaxf(fmaxf(cz[0], cz[1]), fmaxf(cz[2], cz[3])));
-        uint32_t w[4];
-        philox4x32_10((uint32_t)(ccol0 >> 2), row_lo, row_hi, 2u, seed_lo, seed_hi, w);
-        Cand cb{-1.0f, 0x7FFFFFFF};
+                for (int i = kDepth - kAhead; i < kDepth; ++i) {
+                    float z[8];
+                    buf[i % kAhead].unpack(z);
+                    buf[i % kAhead].load(nrowp, next_base + (i + kAhead - kDepth) * kSweepCols);
+                    accumulate_chunk(s, z, c, lane);
+                }
+            } else {
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const bool ok = lane < 32 && ccol0 + j < V;
-            const float q = __builtin_amdgcn_exp2f((cz[j] - zmax) * c) / exp_variate(w[j]);
-            cb = better(cb, Cand{ok ? q : -1.0f, ok ? (int)(ccol0 + j) : 0x7FFFFFFF});
-        }
-        cb = wave_best(cb);
-        tok = cb.idx;
-        if (tok < 0 || tok >= V) tok = 0;                 // only reachable with non-finite input
-        float mine = -INFINITY;
-#pragma unroll
-        for (int j = 0; j < 4; ++j)
-            if (ccol0 + j == tok) mine = cz[j];
-        z_tok = wave_max(mine);
-        if (lane == 0) a.token_out[row] = (int32_t)tok;
-    } else {
-        tok = tgt;
-        z_tok = z_tgt;
-    }
-
-    if (lane == 0) {
-        if (a.entropy_out) a.entropy_out[row] = (float)H;
-        if (a.logp_out) {
-            float lp = __builtin_nanf("");
-            if (tok >= 0 && tok < V)   // ln p = (a_tok - a_peak) - log1p(x)
-                lp = (float)(((double)z_tok - (double)peak) * cd * kLn2 - l1p);
-            a.logp_out[row] = lp;
+                for (int i = kDepth - kAhead; i < kDepth; ++i) {
+                    float z[8];
+                    buf[i % kAhead].unpack(z);
+                    accumulate_chunk(s, z, c, lane);
+                }
+            }
+            close_tile<kSample>(s, st_cur * kLanes + lane, inv_e, true, c, lane);
+            ++held;
+            if (!more || r_next != r_cur) {
+                deliver(s, r_cur, wave, held);
+                fresh(s);
+                held = 0;
+            }
+            if (!more) break;
+            if (r_next != r_cur) {
+                c = row_scale(r_next);
+                rowp = base + r_next * row_bytes;
+            }
+            r_cur = r_next;
+            st_cur = st_next;
         }
     }
 }
@@ -333,34 +410,65 @@ void entropy_reduce_kernel(const float* __restrict__ entropy, const uint8_t* __r
 // ---------------------------------------------------------------------------
 // host-side launchers
 // ---------------------------------------------------------------------------
-template <typename Chunk, bool kSample, int kWaves>
-static hipError_t launch_rows(const VocabPassArgs& a, hipStream_t stream)
+constexpr size_t kLdsBudget = 64 * 1024;
+
+// Rows per workgroup: enough items that the ticket queue can balance the waves (two
+// per wave), at least two rows, and the noise table must fit LDS.  0 = does not fit.
+template <int kWaves>
+static int rows_per_group(int64_t V, bool sample)
 {
-    dim3 grid((unsigned)a.rows), block(kWaves * 64);
-    hipLaunchKernelGGL((vocab_pass_kernel<Chunk, kWaves, kSample>), grid, block, 0, stream, a);
+    const int nst = (int)((V + kSuperCols - 1) / kSuperCols);
+    int rpb = (2 * kWaves + nst - 1) / nst;
+    if (rpb < 2) rpb = 2;
+    while (rpb > 1 && lds_bytes<kWaves>(rpb, nst, sample) > kLdsBudget) --rpb;
+    if (lds_bytes<kWaves>(rpb, nst, sample) > kLdsBudget) return 0;
+    return rpb;
+}
+
+bool vocab_pass_fits(int64_t V) { return rows_per_group<8>(V, true) > 0 && rows_per_group<4>(V, true) > 0; }
+
+static int compute_units()
+{
+    static int cus = 0;
+    if (cus == 0) {
+        int dev = 0;
+        hipDeviceProp_t prop;
+        if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess)
+            cus = prop.multiProcessorCount;
+        if (cus <= 0) cus = 256;
+    }
+    return cus;
+}
+
+template <typename Chunk, bool kSample, int kWaves>
+static hipError_t launch_groups(const VocabPassArgs& a, hipStream_t stream)
+{
+    const int rpb = rows_per_group<kWaves>(a.V, kSample);
+    if (rpb == 0) return hipErrorInvalidValue;
+    const int nst = (int)((a.V + kSuperCols - 1) / kSuperCols);
+    const size_t lds = lds_bytes<kWaves>(rpb, nst, kSample);
+    const unsigned blocks = (unsigned)((a.rows + rpb - 1) / rpb);
+    hipLaunchKernelGGL((vocab_pass_kernel<Chunk, kSample, kWaves, Chunk::kAhead>),
+                       dim3(blocks), dim3(kWaves * 64), lds, stream, a, rpb);
     return hipGetLastError();
 }
 
-// Waves per row.  A row of the 151,936-column vocabulary has 19 super-tiles; four
-// waves share them 5/5/5/4.
-static int pick_waves(const VocabPassArgs& a)
-{
-#ifdef E3_FORCE_WAVES
-    return E3_FORCE_WAVES;
-#else
-    (void)a;
-    return 4;
-#endif
-}
-
+// Eight waves per workgroup while the whole batch is at most four workgroups per
+// compute unit (one CU then holds its share in one or two groups whose waves balance
+// each other through the ticket queue); four waves per workgroup beyond that, where
+// the hardware dispatcher balances across many small groups (measured crossover on
+// MI355X: between 2048 and 4096 rows of 151,936 bf16 columns).
 template <typename Chunk, bool kSample>
 static hipError_t launch_for(const VocabPassArgs& a, hipStream_t stream)
 {
-    switch (pick_waves(a)) {
-        case 16: return launch_rows<Chunk, kSample, 16>(a, stream);
-        case 8: return launch_rows<Chunk, kSample, 8>(a, stream);
-        default: return launch_rows<Chunk, kSample, 4>(a, stream);
-    }
+#ifdef E3_FORCE_WAVES
+    return launch_groups<Chunk, kSample, E3_FORCE_WAVES>(a, stream);
+#else
+    const int rpb8 = rows_per_group<8>(a.V, kSample);
+    if (rpb8 > 0 && (a.rows + rpb8 - 1) / rpb8 <= 4 * (int64_t)compute_units())
+        return launch_groups<Chunk, kSample, 8>(a, stream);
+    return launch_groups<Chunk, kSample, 4>(a, stream);
+#endif
 }
 
 hipError_t launch_vocab_pass(const VocabPassArgs& a, bool is_bf16, bool sample, hipStream_t stream)

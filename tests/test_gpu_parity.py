@@ -282,38 +282,8 @@ def test_advantages_group_shapes():
     assert none.numel() == 0
 
 
-def test_workspace_contract():
-    # one zero-filled workspace serves calls of different shapes and is left zero-filled
-    g = torch.Generator(device=DEV).manual_seed(11)
-    big = (torch.randn((40, 50_000), generator=g, device=DEV) * 3).to(torch.bfloat16)
-    small = (torch.randn((7, 8192 * 2 + 40), generator=g, device=DEV) * 3).float()
-    need = max(e3.e3_workspace_bytes(40, 50_000), e3.e3_workspace_bytes(7, 8192 * 2 + 40))
-    assert need > 0
-    ws = torch.full(((need + 3) // 4,), -1, dtype=torch.int32, device=DEV)
-    e3.e3_workspace_init(ws)
-    assert int(ws.abs().sum()) == 0
-    ref_b = o.sample_entropy(wl.host_bits(big), None, 0.8, 3, 0, nthreads=NT)
-    ref_s = o.logprob_entropy(wl.host_bits(small), None, None, None, 1.1, nthreads=NT)
-    for _ in range(3):
-        tok, lp, en = e3.e3_sample_entropy(big, None, 0.8, 3, 0, workspace=ws)
-        assert int(ws.abs().sum()) == 0
-        keep = ref_b.near_tie == 0
-        assert np.array_equal(tok.cpu().numpy()[keep], ref_b.token[keep])
-        assert close(en.cpu().numpy(), ref_b.entropy).all()
-        _, en2, _, _ = e3.e3_logprob_entropy(small, None, None, None, 1.1, workspace=ws)
-        assert int(ws.abs().sum()) == 0
-        assert close(en2.cpu().numpy(), ref_s.entropy).all()
-    # a problem that needs a workspace refuses to run without one
-    L = e3.lib()
-    tok = torch.empty(40, dtype=torch.int32, device=DEV)
-    rc = L.e3_sample_entropy(big.data_ptr(), 1, 40, 50_000, 50_000, None, 1.0, 1, 0,
-                             tok.data_ptr(), None, None, None, 0, None)
-    assert rc == -6
-
-
-def test_more_rows_than_resident_waves():
-    # 6000 rows x (1 complete + 1 incomplete super-tile): more incomplete pieces than the
-    # launch has waves, so they are also handed out dynamically
+def test_many_short_rows():
+    # 6000 rows x (1 complete + 1 incomplete super-tile): several rows per workgroup
     g = torch.Generator(device=DEV).manual_seed(12)
     lg = (torch.randn((6000, 8192 + 520), generator=g, device=DEV) * 3).to(torch.bfloat16)
     tau = (0.6 + 0.8 * torch.rand(6000, generator=g, device=DEV)).float()
