@@ -4,10 +4,10 @@
 One step = one pass of the whole path over one decode batch of the paper's shape
 (Section 5.1: 64 prompts x 8 rollouts; a 151,936-entry vocabulary, bf16 logits):
 
-  1. e3_sample_entropy   rollout side: token, log-prob, entropy per row      (dominant)
-  2. e3_grpo_advantages  Eq. 2 over the 64 groups of 8 rewards
-  3. e3_logprob_entropy  training side: log-prob of the sampled tokens, entropy,
-                         batch entropy sum/count, on the training-pass logits
+  1. e3_grpo_advantages  Eq. 2 over the 64 groups of 8 rewards
+  2. e3_logprob_entropy  training side: log-prob of the previously sampled tokens,
+                         entropy, batch entropy sum/count, on the training-pass logits
+  3. e3_sample_entropy   rollout side: token, log-prob, entropy per row      (dominant)
   4. 16-byte read-back + e3_temperature_update (Eq. 4 / Eq. 5) on the host
 
 Inputs are resident in HBM before timing starts.  The batch is 156 MB, smaller than
@@ -37,6 +37,10 @@ ROWS = PROMPTS * ROLLOUTS
 HBM_PEAK_GBPS = 8000.0
 # algorithmic bytes of one sampled row: V bf16 logits + tau (4) read, token/logp/entropy (12) written
 BYTES_PER_ROW = V * 2 + 4 + 12
+# HBM bytes per launch of the sample kernel from rocprofv3 FETCH_SIZE + WRITE_SIZE, each scaled by
+# what the same counter reads for a device copy of known size (profiles/…hbm_traffic.txt).
+# Valid for the kernel as profiled; set to None when the kernel changes until re-measured.
+MEASURED_TRAFFIC_BYTES = 157_166_059
 
 
 def main() -> int:
@@ -46,6 +50,10 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--buffers", type=int, default=8, help="distinct logit buffers rotated over")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-probe", action="store_true",
+                    help="also run a plain device copy of one logit buffer 10 times (a kernel of "
+                         "known traffic: 155.6 MB read + 155.6 MB written) so that a rocprofv3 "
+                         "--pmc run can scale FETCH_SIZE / WRITE_SIZE against it")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU: the path has no cross-GPU step (rows are independent); "
@@ -81,22 +89,33 @@ def main() -> int:
     hcnt_host = torch.empty(1, dtype=torch.int64, pin_memory=True)
     ws = e3.new_workspace(ROWS, V, dev)
 
+    if args.copy_probe:
+        dst = torch.empty_like(batches[0].logits)
+        for i in range(10):
+            dst.copy_(batches[i % nb].logits)
+        torch.cuda.synchronize()
+        del dst
+
     state = {"tau": 1.0, "H_init": None, "t": 0}
     stream = torch.cuda.current_stream(dev)
 
     def step(i: int, ev=None):
+        """One cycle of the method.  The order inside a cycle is the loop's own (training
+        pass on the previous rollouts -> scheduler -> next rollouts), rotated so that the
+        sampling call is enqueued while the GPU is still busy: its HIP events then bracket
+        the kernel itself and not the host's launch latency."""
         roll = batches[i % nb]
         train = batches[(i + nb // 2) % nb]
+        e3.e3_grpo_advantages(rewards, offsets, 0, 0.0, adv_out=adv)
+        e3.e3_logprob_entropy(train.logits, tok, None, train.tau_rows, 1.0, logp_out=logp_t,
+                              entropy_out=ent_t, entropy_sum_out=hsum, entropy_count_out=hcnt,
+                              workspace=ws)
         if ev is not None:
             ev[0].record(stream)
         e3.e3_sample_entropy(roll.logits, roll.tau_rows, 1.0, seed=99, row_base=i * ROWS,
                              token_out=tok, logp_out=logp_s, entropy_out=ent_s, workspace=ws)
         if ev is not None:
             ev[1].record(stream)
-        e3.e3_grpo_advantages(rewards, offsets, 0, 0.0, adv_out=adv)
-        e3.e3_logprob_entropy(train.logits, tok, None, train.tau_rows, 1.0, logp_out=logp_t,
-                              entropy_out=ent_t, entropy_sum_out=hsum, entropy_count_out=hcnt,
-                              workspace=ws)
         hsum_host.copy_(hsum, non_blocking=True)
         hcnt_host.copy_(hcnt, non_blocking=True)
         stream.synchronize()
@@ -108,9 +127,20 @@ def main() -> int:
                                                    tau_min=0.05, tau_max=20.0)
         state["t"] += 1
 
+    tok.zero_()                                # targets of the very first training pass
     for i in range(args.warmup):
         step(i)
     torch.cuda.synchronize()
+
+    # what an empty event pair reads on a busy stream (marker packets are not free)
+    probe = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+             for _ in range(50)]
+    for a_ev, b_ev in probe:
+        e3.e3_grpo_advantages(rewards, offsets, 0, 0.0, adv_out=adv)
+        a_ev.record(stream)
+        b_ev.record(stream)
+    torch.cuda.synchronize()
+    pair_ms = sorted(x.elapsed_time(y) for x, y in probe)[len(probe) // 2]
 
     events = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
               for _ in range(args.steps)]
@@ -151,10 +181,12 @@ def main() -> int:
             "avg_ms": kern_avg_ms, "median_ms": kern_ms[len(kern_ms) // 2], "min_ms": kern_ms[0],
             "rows_per_s": ROWS / (kern_avg_ms * 1e-3),
             "timing": "HIP events on the launch stream around e3_sample_entropy, every timed step",
+            "empty_event_pair_ms": pair_ms,
+            "avg_ms_minus_empty_pair": kern_avg_ms - pair_ms,
         },
         "roofline": {
             "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-            "frac": achieved / HBM_PEAK_GBPS, "traffic": None,
+            "frac": achieved / HBM_PEAK_GBPS, "traffic": MEASURED_TRAFFIC_BYTES,
             "kernel": "vocab_pass_kernel<bf16, sample>",
         },
         "scheduler": {"tau_after": state["tau"], "H_init": state["H_init"]},
