@@ -230,7 +230,10 @@ void vocab_pass_kernel(VocabPassArgs a, int rpb)
             reinterpret_cast<float4*>(inv_e_tab)[(size_t)r * nst * 16 + rem] = v;
         }
     }
-    __syncthreads();
+    // Workgroup barrier that orders LDS only: __syncthreads() would also wait for the
+    // global loads already in flight (its fence covers global memory) and drain the
+    // pipeline for a full memory latency.
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
 
     auto take_ticket = [&]() -> int {
         uint32_t t = 0;
