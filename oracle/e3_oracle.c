@@ -422,3 +422,107 @@ int e3o_max_threads(void)
     return 1;
 #endif
 }
+
+/* ======================================================================== */
+/* Dynamic rollout budget (Section 4.1, Algorithm 1)                         */
+/* ======================================================================== */
+
+/*
+ * Difficulty ranking, Section 4.1: questions are ranked by their average reward
+ * r_c / n_c in descending order; k_i = rank(q_i) / |D|, rank counted from 1, so the
+ * question with the lowest average reward gets k = 1 (hardest).  Readings: equal
+ * averages keep their index order (the lower index ranks first); a question with no
+ * rollouts yet counts as average reward 0.
+ */
+int e3o_difficulty_ranks(const double *cum_reward, const int64_t *cum_rollouts, int64_t n,
+                         double *k_out)
+{
+    if (n < 0) return -2;
+    for (int64_t i = 0; i < n; ++i) {
+        if (cum_rollouts[i] < 0) return -5;
+        double avg_i = cum_rollouts[i] > 0 ? cum_reward[i] / (double)cum_rollouts[i] : 0.0;
+        if (!(avg_i == avg_i)) return -5;
+        int64_t ahead = 0;                    /* questions that rank before i */
+        for (int64_t j = 0; j < n; ++j) {
+            if (j == i) continue;
+            double avg_j = cum_rollouts[j] > 0 ? cum_reward[j] / (double)cum_rollouts[j] : 0.0;
+            if (avg_j > avg_i || (avg_j == avg_i && j < i)) ++ahead;
+        }
+        k_out[i] = (double)(ahead + 1) / (double)n;
+    }
+    return 0;
+}
+
+/*
+ * Algorithm 1.  N_total = B*G; every question starts at G_min; the remaining
+ * N_total - B*G_min rollouts are split in proportion to k_i, rounded down; what the
+ * rounding leaves over is handed out greedily in descending order of k, never above
+ * G_max.  The batch total stays B*G.  Readings: the proportional step is capped at
+ * G_max (the printed step can exceed it); "greedily" = passes over the questions in
+ * descending k (ties: lower index first), one rollout per question per pass, skipping
+ * those at G_max, until nothing is left.  Needs G_min <= G <= G_max, k_i finite >= 0
+ * and sum k > 0.
+ */
+int e3o_allocate_budgets(const double *k, int32_t B, int32_t G, int32_t G_min, int32_t G_max,
+                         int32_t *G_out)
+{
+    if (B < 0) return -2;
+    if (G_min < 0 || G_min > G || G > G_max) return -5;
+    if (B == 0) return 0;
+    double sum_k = 0.0;
+    for (int32_t i = 0; i < B; ++i) {
+        if (!(k[i] >= 0.0) || !isfinite(k[i])) return -5;
+        sum_k += k[i];
+    }
+    if (!(sum_k > 0.0)) return -5;
+    int64_t total = (int64_t)B * G;
+    int64_t rem = total - (int64_t)B * G_min;
+    int64_t used = 0;
+    for (int32_t i = 0; i < B; ++i) {
+        int64_t extra = (int64_t)floor((double)rem * k[i] / sum_k);
+        int64_t g = (int64_t)G_min + extra;
+        if (g > G_max) g = G_max;
+        G_out[i] = (int32_t)g;
+        used += g;
+    }
+    int64_t left = total - used;
+    /* order of descending k, ties by index: selection sort on an index array */
+    int32_t *order = (int32_t *)malloc((size_t)B * sizeof(int32_t));
+    if (!order) return -1;
+    for (int32_t i = 0; i < B; ++i) order[i] = i;
+    for (int32_t a = 0; a < B; ++a) {
+        int32_t best = a;
+        for (int32_t b = a + 1; b < B; ++b) {
+            int32_t x = order[b], y = order[best];
+            if (k[x] > k[y] || (k[x] == k[y] && x < y)) best = b;
+        }
+        int32_t t = order[a]; order[a] = order[best]; order[best] = t;
+    }
+    while (left > 0) {
+        int64_t before = left;
+        for (int32_t a = 0; a < B && left > 0; ++a) {
+            int32_t i = order[a];
+            if (G_out[i] < G_max) { G_out[i] += 1; left -= 1; }
+        }
+        if (left == before) break;             /* cannot happen while G <= G_max */
+    }
+    free(order);
+    return left == 0 ? 0 : -5;
+}
+
+/*
+ * Bounds curriculum (end of Section 4.1; Section 5.3 uses +-2 per pass over the
+ * data): both bounds start at G; after each completed pass G_max grows and G_min
+ * shrinks by `step` until they reach their limits.
+ */
+int e3o_budget_bounds(int32_t G, int32_t passes_done, int32_t step, int32_t G_min_limit,
+                      int32_t G_max_limit, int32_t *G_min_out, int32_t *G_max_out)
+{
+    if (G < 0 || passes_done < 0 || step < 0 || G_min_limit < 0 || G_min_limit > G || G_max_limit < G)
+        return -5;
+    int64_t lo = (int64_t)G - (int64_t)step * passes_done;
+    int64_t hi = (int64_t)G + (int64_t)step * passes_done;
+    *G_min_out = (int32_t)(lo < G_min_limit ? G_min_limit : lo);
+    *G_max_out = (int32_t)(hi > G_max_limit ? G_max_limit : hi);
+    return 0;
+}

@@ -63,6 +63,12 @@ def _declare(L):
     L.e3o_entropy_target.restype = f64
     L.e3o_temperature_update.argtypes = [f64, f64, f64, i64, i64, i64, i64, f64, f64, f64, vp, vp]
     L.e3o_temperature_update.restype = C.c_int
+    L.e3o_difficulty_ranks.argtypes = [vp, vp, i64, vp]
+    L.e3o_difficulty_ranks.restype = C.c_int
+    L.e3o_allocate_budgets.argtypes = [vp, i32, i32, i32, i32, vp]
+    L.e3o_allocate_budgets.restype = C.c_int
+    L.e3o_budget_bounds.argtypes = [i32, i32, i32, i32, i32, vp, vp]
+    L.e3o_budget_bounds.restype = C.c_int
     L.e3o_max_threads.argtypes = []
     L.e3o_max_threads.restype = C.c_int
 
@@ -218,6 +224,31 @@ def temperature_update(tau_t: float, H_t: float, H_init: float, vocab: int, t: i
     rc = lib().e3o_temperature_update(tau_t, H_t, H_init, vocab, t, t_anneal, t_max, eta,
                                       tau_min, tau_max, C.addressof(nxt), C.addressof(tgt))
     return rc, nxt.value, tgt.value
+
+
+def difficulty_ranks(cum_reward, cum_rollouts):
+    """Returns (status, k float64 [n])."""
+    r = np.ascontiguousarray(cum_reward, dtype=np.float64)
+    n = np.ascontiguousarray(cum_rollouts, dtype=np.int64)
+    k = np.full(r.shape[0], np.nan)
+    rc = lib().e3o_difficulty_ranks(_ptr(r), _ptr(n), r.shape[0], _ptr(k))
+    return rc, k
+
+
+def allocate_budgets(k, G: int, G_min: int, G_max: int):
+    """Returns (status, G_i int32 [B])."""
+    k = np.ascontiguousarray(k, dtype=np.float64)
+    out = np.full(k.shape[0], -1, dtype=np.int32)
+    rc = lib().e3o_allocate_budgets(_ptr(k), k.shape[0], G, G_min, G_max, _ptr(out))
+    return rc, out
+
+
+def budget_bounds(G: int, passes_done: int, step: int, G_min_limit: int, G_max_limit: int):
+    """Returns (status, G_min, G_max)."""
+    lo, hi = C.c_int32(-1), C.c_int32(-1)
+    rc = lib().e3o_budget_bounds(G, passes_done, step, G_min_limit, G_max_limit,
+                                 C.addressof(lo), C.addressof(hi))
+    return rc, lo.value, hi.value
 
 
 def max_threads() -> int:
