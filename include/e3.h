@@ -165,6 +165,40 @@ int e3_temperature_update(double tau_t, double H_t, double H_init, int64_t vocab
                           double tau_min, double tau_max,
                           double* tau_next_out, double* H_target_out);
 
+/*
+ * Difficulty ranking of the training questions, host only (Section 4.1): questions
+ * are ranked by average reward cum_reward[i] / cum_rollouts[i] in descending order
+ * and k_i = rank / num_questions, rank counted from 1, so the question answered worst
+ * gets k = 1.  Equal averages rank in index order; a question with no rollouts yet
+ * counts as average 0.  All pointers are HOST arrays of num_questions entries.
+ * E3_ERR_VALUE for a negative rollout count or a NaN average.
+ */
+int e3_difficulty_ranks(const double* cum_reward, const int64_t* cum_rollouts,
+                        int64_t num_questions, double* k_out);
+
+/*
+ * Algorithm 1 (Dynamic Rollout Budget), host only.  Given the normalised rankings
+ * k[B] of a batch, the default budget G and the bounds G_min <= G <= G_max: every
+ * question starts at G_min, the remaining B*G - B*G_min rollouts are split in
+ * proportion to k_i (rounded down, capped at G_max), and what is left over is handed
+ * out in passes over the questions in descending k (ties: lower index first), one
+ * rollout per question per pass, skipping questions at G_max.  sum G_out = B*G.
+ * G_out       [B] int32 (host).
+ * offsets_out [B+1] int32 (host) or NULL: the CSR group offsets (prefix sums of
+ *             G_out) in the form e3_grpo_advantages takes.
+ * E3_ERR_VALUE unless G_min <= G <= G_max, k finite and >= 0 with a positive sum.
+ */
+int e3_allocate_budgets(const double* k, int32_t B, int32_t G, int32_t G_min, int32_t G_max,
+                        int32_t* G_out, int32_t* offsets_out);
+
+/*
+ * Bounds curriculum, host only (end of Section 4.1): G_min and G_max start at G and
+ * after each completed pass over the data move outwards by `step` until they reach
+ * G_min_limit / G_max_limit (the paper's runs: G = 8, step 2, limits 4 and 12).
+ */
+int e3_budget_bounds(int32_t G, int32_t passes_done, int32_t step, int32_t G_min_limit,
+                     int32_t G_max_limit, int32_t* G_min_out, int32_t* G_max_out);
+
 #ifdef __cplusplus
 }
 #endif

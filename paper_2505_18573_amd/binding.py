@@ -21,7 +21,8 @@ E3_OK = 0
 E3_TILE_CHUNK, E3_TILE_LANES, E3_TILE_DEPTH = 8, 64, 16
 
 EXPORTS = ("e3_strerror", "e3_workspace_bytes", "e3_sample_entropy", "e3_logprob_entropy",
-           "e3_grpo_advantages", "e3_temperature_update")
+           "e3_grpo_advantages", "e3_temperature_update", "e3_difficulty_ranks",
+           "e3_allocate_budgets", "e3_budget_bounds")
 
 _lib: Optional[C.CDLL] = None
 
@@ -55,6 +56,12 @@ def lib() -> C.CDLL:
         L.e3_grpo_advantages.restype = C.c_int
         L.e3_temperature_update.argtypes = [f64, f64, f64, i64, i64, i64, i64, f64, f64, f64, vp, vp]
         L.e3_temperature_update.restype = C.c_int
+        L.e3_difficulty_ranks.argtypes = [vp, vp, i64, vp]
+        L.e3_difficulty_ranks.restype = C.c_int
+        L.e3_allocate_budgets.argtypes = [vp, i32, i32, i32, i32, vp, vp]
+        L.e3_allocate_budgets.restype = C.c_int
+        L.e3_budget_bounds.argtypes = [i32, i32, i32, i32, i32, vp, vp]
+        L.e3_budget_bounds.restype = C.c_int
         _lib = L
     return _lib
 
@@ -213,3 +220,41 @@ def e3_temperature_update(tau_t: float, H_t: float, H_init: float, vocab: int, t
     if rc != E3_OK:
         raise E3Error(rc, "e3_temperature_update")
     return nxt.value, tgt.value
+
+
+def e3_difficulty_ranks(cum_reward, cum_rollouts):
+    """Host-only.  Returns k (numpy float64 [num_questions])."""
+    import numpy as np
+    r = np.ascontiguousarray(cum_reward, dtype=np.float64)
+    n = np.ascontiguousarray(cum_rollouts, dtype=np.int64)
+    if r.shape != n.shape or r.ndim != 1:
+        raise ValueError("cum_reward and cum_rollouts must be 1-D and of equal length")
+    k = np.empty(r.shape[0], dtype=np.float64)
+    rc = lib().e3_difficulty_ranks(r.ctypes.data, n.ctypes.data, r.shape[0], k.ctypes.data)
+    if rc != E3_OK:
+        raise E3Error(rc, "e3_difficulty_ranks")
+    return k
+
+
+def e3_allocate_budgets(k, G: int, G_min: int, G_max: int):
+    """Host-only.  Returns (G_i int32 [B], offsets int32 [B+1]) as numpy arrays."""
+    import numpy as np
+    k = np.ascontiguousarray(k, dtype=np.float64)
+    B = k.shape[0]
+    g = np.empty(B, dtype=np.int32)
+    off = np.empty(B + 1, dtype=np.int32)
+    rc = lib().e3_allocate_budgets(k.ctypes.data, B, int(G), int(G_min), int(G_max),
+                                   g.ctypes.data, off.ctypes.data)
+    if rc != E3_OK:
+        raise E3Error(rc, "e3_allocate_budgets")
+    return g, off
+
+
+def e3_budget_bounds(G: int, passes_done: int, step: int, G_min_limit: int, G_max_limit: int):
+    """Host-only.  Returns (G_min, G_max)."""
+    lo, hi = C.c_int32(-1), C.c_int32(-1)
+    rc = lib().e3_budget_bounds(int(G), int(passes_done), int(step), int(G_min_limit),
+                                int(G_max_limit), C.addressof(lo), C.addressof(hi))
+    if rc != E3_OK:
+        raise E3Error(rc, "e3_budget_bounds")
+    return lo.value, hi.value
