@@ -526,3 +526,73 @@ int e3o_budget_bounds(int32_t G, int32_t passes_done, int32_t step, int32_t G_mi
     *G_max_out = (int32_t)(hi > G_max_limit ? G_max_limit : hi);
     return 0;
 }
+
+/* ======================================================================== */
+/* Logit gap Delta measured from the logits (Appendix A)                     */
+/* ======================================================================== */
+
+/*
+ * Appendix A models a low-entropy row as one dominant logit z_max and all others a
+ * common gap Delta below it, and notes that Delta could be estimated from the logits
+ * (the paper then replaces it by ln N + ln ln N to avoid the extra pass).  Reading of
+ * "estimate Delta from the logits": the probability-weighted mean gap of the
+ * non-maximal tokens,
+ *     Delta_hat = sum_{i != i*} p_i (z_max - z_i) / sum_{i != i*} p_i,
+ * i* = the first index attaining the maximum, p = softmax(z / tau).  It equals Delta
+ * exactly on the two-level model for every tau, and it is the quantity tied to the
+ * entropy by the appendix's decomposition: H = beta (1 - p_max) Delta_hat + ln Z.
+ * A row with a single column has no rest: Delta_hat = NaN.
+ */
+int e3o_logit_gaps(const void *logits, int dtype, int64_t rows, int64_t V, int64_t row_stride,
+                   const float *tau_rows, float tau_scalar, double *gap_out)
+{
+    if (!logits || rows < 0 || V < 1 || (row_stride < V && row_stride != 0)) return -1;
+    size_t esz = dtype == E3O_F32 ? 4 : 2;
+    for (int64_t r = 0; r < rows; ++r) {
+        const void *row = (const char *)logits + (size_t)r * (size_t)row_stride * esz;
+        double tau = row_tau(tau_rows, tau_scalar, r);
+        double zmax = -INFINITY;
+        int64_t imax = 0;
+        for (int64_t i = 0; i < V; ++i) {
+            double z = load_logit(row, dtype, (size_t)i);
+            if (z > zmax) { zmax = z; imax = i; }
+        }
+        double mass = 0.0, weighted = 0.0;
+        for (int64_t i = 0; i < V; ++i) {
+            if (i == imax) continue;
+            double gap = zmax - load_logit(row, dtype, (size_t)i);
+            double e = exp(-gap / tau);               /* p_i up to the common factor 1/Z */
+            mass += e;
+            weighted += gap * e;
+        }
+        gap_out[r] = mass > 0.0 ? weighted / mass : NAN;
+    }
+    return 0;
+}
+
+/*
+ * Temperature update with a measured gap, Appendix A's relation before the
+ * ln N + ln ln N substitution:  tau' = tau (1 + tau ln(alpha) / Delta),
+ * alpha = H_target / H_t with the same target as Eq. 4 / Eq. 5.  Delta must be
+ * finite and > 0; other guards as in e3o_temperature_update.
+ */
+int e3o_temperature_update_gap(double tau_t, double H_t, double H_init, double delta,
+                               int64_t t, int64_t t_anneal, int64_t t_max, double eta,
+                               double tau_min, double tau_max,
+                               double *tau_next_out, double *H_target_out)
+{
+    if (!tau_next_out) return -1;
+    if (!(tau_t > 0.0) || !isfinite(tau_t) || !(H_t > 0.0) || !isfinite(H_t) ||
+        !(H_init > 0.0) || !isfinite(H_init) || !(delta > 0.0) || !isfinite(delta) ||
+        !(eta >= 0.0 && eta <= 1.0) || !(tau_min >= 0.0) || !(tau_max >= tau_min))
+        return -5;
+    double target = e3o_entropy_target(H_init, t, t_anneal, t_max, eta);
+    if (!(target > 0.0)) return -5;
+    double next = tau_t * (1.0 + tau_t * log(target / H_t) / delta);
+    if (!(next > 0.0) && !(tau_min > 0.0)) return -5;
+    if (next < tau_min) next = tau_min;
+    if (next > tau_max) next = tau_max;
+    *tau_next_out = next;
+    if (H_target_out) *H_target_out = target;
+    return 0;
+}

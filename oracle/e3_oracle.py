@@ -69,6 +69,10 @@ def _declare(L):
     L.e3o_allocate_budgets.restype = C.c_int
     L.e3o_budget_bounds.argtypes = [i32, i32, i32, i32, i32, vp, vp]
     L.e3o_budget_bounds.restype = C.c_int
+    L.e3o_logit_gaps.argtypes = [vp, C.c_int, i64, i64, i64, vp, f32, vp]
+    L.e3o_logit_gaps.restype = C.c_int
+    L.e3o_temperature_update_gap.argtypes = [f64, f64, f64, f64, i64, i64, i64, f64, f64, f64, vp, vp]
+    L.e3o_temperature_update_gap.restype = C.c_int
     L.e3o_max_threads.argtypes = []
     L.e3o_max_threads.restype = C.c_int
 
@@ -249,6 +253,28 @@ def budget_bounds(G: int, passes_done: int, step: int, G_min_limit: int, G_max_l
     rc = lib().e3o_budget_bounds(G, passes_done, step, G_min_limit, G_max_limit,
                                  C.addressof(lo), C.addressof(hi))
     return rc, lo.value, hi.value
+
+
+def logit_gaps(logits: np.ndarray, tau_rows: Optional[np.ndarray], tau_scalar: float) -> np.ndarray:
+    dt, rows, V, stride = _logits(logits)
+    if tau_rows is not None:
+        tau_rows = np.ascontiguousarray(tau_rows, dtype=np.float32)
+    out = np.empty(rows, dtype=np.float64)
+    rc = lib().e3o_logit_gaps(_ptr(logits), dt, rows, V, stride, _ptr(tau_rows), tau_scalar, _ptr(out))
+    if rc != 0:
+        raise RuntimeError(f"e3o_logit_gaps failed: {rc}")
+    return out
+
+
+def temperature_update_gap(tau_t: float, H_t: float, H_init: float, delta: float, t: int = 0,
+                           t_anneal: int = -1, t_max: int = 0, eta: float = 1.0,
+                           tau_min: float = 0.0, tau_max: float = float("inf")):
+    """Returns (status, tau_next, H_target)."""
+    nxt = C.c_double(float("nan"))
+    tgt = C.c_double(float("nan"))
+    rc = lib().e3o_temperature_update_gap(tau_t, H_t, H_init, delta, t, t_anneal, t_max, eta,
+                                          tau_min, tau_max, C.addressof(nxt), C.addressof(tgt))
+    return rc, nxt.value, tgt.value
 
 
 def max_threads() -> int:
