@@ -127,6 +127,26 @@ int e3_logprob_entropy(const void* logits, int dtype, int64_t rows, int64_t V, i
                        void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /*
+ * e3_logprob_entropy that also measures, in the same pass, the logit gap Delta of
+ * Appendix A on every row: the paper's update is tau1 = tau0 (1 + tau0 ln(alpha) /
+ * Delta) and it replaces Delta by ln N + ln ln N only because measuring it would cost
+ * another pass over the logits; here it is a by-product of the sums already taken.
+ *   gap_r = sum_{i != i*} p_i (z_max - z_i) / sum_{i != i*} p_i        (logit units)
+ * with i* one index attaining the row maximum and p = softmax(z / tau_r); it equals
+ * Delta exactly on the appendix's two-level model and satisfies the appendix's
+ * decomposition H = beta (1 - p_max) gap + ln Z.  A one-column row gives NaN.
+ * gap_out      [rows] fp32 or NULL.
+ * gap_sum_out  one double (device) or NULL (needs gap_out): sum of gap_out over kept
+ *              rows, fp64, fixed order.  count_out as entropy_count_out.
+ */
+int e3_logprob_entropy_gap(const void* logits, int dtype, int64_t rows, int64_t V, int64_t row_stride,
+                           const int32_t* target_ids, const uint8_t* row_mask,
+                           const float* tau_rows, float tau_scalar,
+                           float* logp_out, float* entropy_out, float* gap_out,
+                           double* entropy_sum_out, double* gap_sum_out, int64_t* count_out,
+                           void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
  * Group-relative advantage, Eq. 2:  A_i = (r_i - mean(r)) / std(r) over the
  * rollouts of one prompt, groups stored CSR-style because Algorithm 1 gives each
  * prompt its own rollout budget.
@@ -164,6 +184,17 @@ int e3_temperature_update(double tau_t, double H_t, double H_init, int64_t vocab
                           int64_t t, int64_t t_anneal, int64_t t_max, double eta,
                           double tau_min, double tau_max,
                           double* tau_next_out, double* H_target_out);
+
+/*
+ * The same update with a measured gap instead of ln|V| + ln ln|V| (Appendix A, the
+ * relation tau1 = tau0 (1 + tau0 ln(alpha) / Delta)); host only.  `gap` is the batch
+ * mean of e3_logprob_entropy_gap's gap_out and must be finite and > 0; all else as
+ * e3_temperature_update.
+ */
+int e3_temperature_update_gap(double tau_t, double H_t, double H_init, double gap,
+                              int64_t t, int64_t t_anneal, int64_t t_max, double eta,
+                              double tau_min, double tau_max,
+                              double* tau_next_out, double* H_target_out);
 
 /*
  * Difficulty ranking of the training questions, host only (Section 4.1): questions

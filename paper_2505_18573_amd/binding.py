@@ -22,7 +22,8 @@ E3_TILE_CHUNK, E3_TILE_LANES, E3_TILE_DEPTH = 8, 64, 16
 
 EXPORTS = ("e3_strerror", "e3_workspace_bytes", "e3_sample_entropy", "e3_logprob_entropy",
            "e3_grpo_advantages", "e3_temperature_update", "e3_difficulty_ranks",
-           "e3_allocate_budgets", "e3_budget_bounds")
+           "e3_allocate_budgets", "e3_budget_bounds", "e3_logprob_entropy_gap",
+           "e3_temperature_update_gap")
 
 _lib: Optional[C.CDLL] = None
 
@@ -52,6 +53,11 @@ def lib() -> C.CDLL:
         L.e3_logprob_entropy.argtypes = [vp, C.c_int, i64, i64, i64, vp, vp, vp, f32,
                                          vp, vp, vp, vp, vp, C.c_size_t, vp]
         L.e3_logprob_entropy.restype = C.c_int
+        L.e3_logprob_entropy_gap.argtypes = [vp, C.c_int, i64, i64, i64, vp, vp, vp, f32,
+                                             vp, vp, vp, vp, vp, vp, vp, C.c_size_t, vp]
+        L.e3_logprob_entropy_gap.restype = C.c_int
+        L.e3_temperature_update_gap.argtypes = [f64, f64, f64, f64, i64, i64, i64, f64, f64, f64, vp, vp]
+        L.e3_temperature_update_gap.restype = C.c_int
         L.e3_grpo_advantages.argtypes = [vp, vp, i32, i32, f32, vp, vp]
         L.e3_grpo_advantages.restype = C.c_int
         L.e3_temperature_update.argtypes = [f64, f64, f64, i64, i64, i64, i64, f64, f64, f64, vp, vp]
@@ -258,3 +264,42 @@ def e3_budget_bounds(G: int, passes_done: int, step: int, G_min_limit: int, G_ma
     if rc != E3_OK:
         raise E3Error(rc, "e3_budget_bounds")
     return lo.value, hi.value
+
+
+def e3_logprob_entropy_gap(logits: torch.Tensor, target_ids: Optional[torch.Tensor],
+                           row_mask: Optional[torch.Tensor], tau_rows: Optional[torch.Tensor],
+                           tau_scalar: float, workspace: Optional[torch.Tensor] = None):
+    """Returns (logp or None, entropy, gap, entropy_sum fp64 [1], gap_sum fp64 [1], count int64 [1]),
+    all on the device."""
+    dt, rows, V, stride = _logits_meta(logits)
+    dev = logits.device
+    logp = torch.empty(rows, dtype=torch.float32, device=dev) if target_ids is not None else None
+    ent = torch.empty(rows, dtype=torch.float32, device=dev)
+    gap = torch.empty(rows, dtype=torch.float32, device=dev)
+    hs = torch.empty(1, dtype=torch.float64, device=dev)
+    gs = torch.empty(1, dtype=torch.float64, device=dev)
+    cnt = torch.empty(1, dtype=torch.int64, device=dev)
+    _check(target_ids, torch.int32, rows, "target_ids", dev)
+    _check(row_mask, torch.uint8, rows, "row_mask", dev)
+    _check(tau_rows, torch.float32, rows, "tau_rows", dev)
+    ws, ws_bytes = _workspace(rows, V, workspace, dev)
+    rc = lib().e3_logprob_entropy_gap(_ptr(logits), dt, rows, V, stride, _ptr(target_ids),
+                                      _ptr(row_mask), _ptr(tau_rows), float(tau_scalar),
+                                      _ptr(logp), _ptr(ent), _ptr(gap), _ptr(hs), _ptr(gs), _ptr(cnt),
+                                      _ptr(ws), ws_bytes, _stream(dev))
+    if rc != E3_OK:
+        raise E3Error(rc, "e3_logprob_entropy_gap")
+    return logp, ent, gap, hs, gs, cnt
+
+
+def e3_temperature_update_gap(tau_t: float, H_t: float, H_init: float, gap: float, t: int = 0,
+                              t_anneal: int = -1, t_max: int = 0, eta: float = 1.0,
+                              tau_min: float = 0.0, tau_max: float = float("inf")):
+    """Host-only scheduler step with a measured gap.  Returns (tau_next, H_target)."""
+    nxt, tgt = C.c_double(float("nan")), C.c_double(float("nan"))
+    rc = lib().e3_temperature_update_gap(float(tau_t), float(H_t), float(H_init), float(gap), int(t),
+                                         int(t_anneal), int(t_max), float(eta), float(tau_min),
+                                         float(tau_max), C.addressof(nxt), C.addressof(tgt))
+    if rc != E3_OK:
+        raise E3Error(rc, "e3_temperature_update_gap")
+    return nxt.value, tgt.value

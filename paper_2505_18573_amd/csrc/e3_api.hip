@@ -76,12 +76,13 @@ extern "C" int e3_sample_entropy(const void* logits, int dtype, int64_t rows, in
     return err == hipSuccess ? E3_OK : E3_ERR_LAUNCH;
 }
 
-extern "C" int e3_logprob_entropy(const void* logits, int dtype, int64_t rows, int64_t V,
-                                  int64_t row_stride, const int32_t* target_ids,
-                                  const uint8_t* row_mask, const float* tau_rows, float tau_scalar,
-                                  float* logp_out, float* entropy_out,
-                                  double* entropy_sum_out, int64_t* entropy_count_out,
-                                  void* workspace, size_t workspace_bytes, void* hip_stream)
+extern "C" int e3_logprob_entropy_gap(const void* logits, int dtype, int64_t rows, int64_t V,
+                                      int64_t row_stride, const int32_t* target_ids,
+                                      const uint8_t* row_mask, const float* tau_rows, float tau_scalar,
+                                      float* logp_out, float* entropy_out, float* gap_out,
+                                      double* entropy_sum_out, double* gap_sum_out,
+                                      int64_t* count_out,
+                                      void* workspace, size_t workspace_bytes, void* hip_stream)
 {
     int rc = check_logits(logits, dtype, rows, V, row_stride);
     if (rc != E3_OK) return rc;
@@ -89,6 +90,7 @@ extern "C" int e3_logprob_entropy(const void* logits, int dtype, int64_t rows, i
     if (rc != E3_OK) return rc;
     if (rows > 0 && entropy_out == nullptr) return E3_ERR_NULL;
     if (logp_out != nullptr && target_ids == nullptr) return E3_ERR_NULL;
+    if (gap_sum_out != nullptr && gap_out == nullptr) return E3_ERR_NULL;
     (void)workspace; (void)workspace_bytes;
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
 
@@ -98,16 +100,33 @@ extern "C" int e3_logprob_entropy(const void* logits, int dtype, int64_t rows, i
         a.tau_rows = tau_rows; a.tau_scalar = tau_scalar;
         a.target_ids = target_ids;
         a.token_out = nullptr; a.logp_out = logp_out; a.entropy_out = entropy_out;
+        a.gap_out = gap_out;
         if (e3::launch_vocab_pass(a, dtype == E3_BF16, false, stream) != hipSuccess)
             return E3_ERR_LAUNCH;
     }
-    if (entropy_sum_out != nullptr || entropy_count_out != nullptr) {
-        // also for rows == 0: the sum and the count are then written as 0
-        if (e3::launch_entropy_reduce(entropy_out, row_mask, rows, entropy_sum_out,
-                                      entropy_count_out, stream) != hipSuccess)
+    // also for rows == 0: sums and count are then written as 0
+    if (entropy_sum_out != nullptr || count_out != nullptr) {
+        if (e3::launch_entropy_reduce(entropy_out, row_mask, rows, entropy_sum_out, count_out,
+                                      stream) != hipSuccess)
+            return E3_ERR_LAUNCH;
+    }
+    if (gap_sum_out != nullptr) {
+        if (e3::launch_entropy_reduce(gap_out, row_mask, rows, gap_sum_out, nullptr, stream) != hipSuccess)
             return E3_ERR_LAUNCH;
     }
     return E3_OK;
+}
+
+extern "C" int e3_logprob_entropy(const void* logits, int dtype, int64_t rows, int64_t V,
+                                  int64_t row_stride, const int32_t* target_ids,
+                                  const uint8_t* row_mask, const float* tau_rows, float tau_scalar,
+                                  float* logp_out, float* entropy_out,
+                                  double* entropy_sum_out, int64_t* entropy_count_out,
+                                  void* workspace, size_t workspace_bytes, void* hip_stream)
+{
+    return e3_logprob_entropy_gap(logits, dtype, rows, V, row_stride, target_ids, row_mask, tau_rows,
+                                  tau_scalar, logp_out, entropy_out, nullptr, entropy_sum_out, nullptr,
+                                  entropy_count_out, workspace, workspace_bytes, hip_stream);
 }
 
 extern "C" int e3_grpo_advantages(const float* rewards, const int32_t* group_offsets,

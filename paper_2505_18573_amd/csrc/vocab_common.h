@@ -247,7 +247,7 @@ struct ChunkF32 {
 // Running state of one wave.  rc, top, dom_lane and dom_open are wave-uniform.
 // All sums are in base-2 units relative to rc:  t = z*c - rc,  e = 2^t.
 //
-// The largest logit the wave has met so far (`top`, the one that last moved the
+// The largest logit the wave has met so far (`top`; every new one moves the
 // reference) is kept OUT of the fp32 sums and carried as a scalar.  On a peaked row
 // that term is ~1 while all others together may be 1e-4 or less; inside an fp32
 // accumulator it would swallow their low bits (absolute error ~1e-7), kept apart the
@@ -271,7 +271,7 @@ struct LaneState {
 // Real logits are required to be far above it (|z| < 1e30).
 constexpr float kAbsent = -1.0e30f;
 
-// A sweep holds a logit above the wave's reference.  Move the reference to
+// A sweep holds a logit above the wave's running maximum.  Move the reference to
 // ceil(new top * c): the shift d is a non-negative integer, so scaling by 2^-d is
 // exact.  The previous top becomes an ordinary term of the lane that held it; the new
 // one is struck from its chunk.
@@ -314,9 +314,9 @@ __device__ __forceinline__ void new_maximum(LaneState& s, float z[8], float chun
 __device__ __forceinline__ void accumulate_chunk(LaneState& s, float z[8], float c, int lane)
 {
     const float cm = fmax3(fmax3(z[0], z[1], z[2]), fmax3(z[3], z[4], z[5]), fmax3(z[6], z[7], z[7]));
-    // t_max > 0: the reference no longer covers this sweep (always so while rc = -inf)
-    const float tmax = fmaf(cm, c, -s.rc);
-    if (__builtin_expect(__any(tmax > 0.0f), 0)) new_maximum(s, z, cm, c, lane);
+    // A logit above everything the wave has met moves the reference (always so before
+    // the first element); `top` is thus the exact running maximum of the wave.
+    if (__builtin_expect(__any(cm > s.top), 0)) new_maximum(s, z, cm, c, lane);
     const float nrc = -s.rc;
 #pragma unroll
     for (int j = 0; j < 8; ++j) {

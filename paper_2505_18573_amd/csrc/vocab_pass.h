@@ -15,6 +15,7 @@ struct VocabPassArgs {
     int32_t* token_out;               // sampling only
     float* logp_out;                  // nullable
     float* entropy_out;               // nullable
+    float* gap_out;                   // nullable: measured logit gap (Appendix A's Delta)
 };
 
 hipError_t launch_vocab_pass(const VocabPassArgs& a, bool is_bf16, bool sample, hipStream_t stream);

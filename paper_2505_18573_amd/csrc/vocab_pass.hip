@@ -151,6 +151,12 @@ __device__ __forceinline__ void finish_row(const VocabPassArgs& a, int64_t row,
     }
     if (lane == 0) {
         if (a.entropy_out) a.entropy_out[row] = (float)H;
+        if (a.gap_out) {
+            // Appendix A's Delta measured on this row: the probability-weighted mean of
+            // z_peak - z_i over all other tokens = tau ln2 (t_p - W_rest / S_rest)
+            a.gap_out[row] = S_rest > 0.0 ? (float)((double)tau * kLn2 * (t_p - W_rest / S_rest))
+                                          : __builtin_nanf("");
+        }
         if (a.logp_out) {
             float lp = __builtin_nanf("");
             if (tok >= 0 && tok < V)   // ln p = (a_tok - a_peak) - log1p(x)
