@@ -596,3 +596,49 @@ int e3o_temperature_update_gap(double tau_t, double H_t, double H_init, double d
     if (H_target_out) *H_target_out = target;
     return 0;
 }
+
+/* ======================================================================== */
+/* GRPO clipped objective, Eq. 1 (forward value only)                        */
+/* ======================================================================== */
+
+/*
+ * J = mean over questions q of (1/G_q) sum_{i in q} (1/|o_i|) sum_t
+ *         min( r_{i,t} A_i , clip(r_{i,t}, 1-eps, 1+eps) A_i ),
+ * r_{i,t} = pi_theta / pi_theta_old = exp(logp_new - logp_old) of token t of rollout i,
+ * A_i the rollout's advantage (Eq. 2; the same for all its tokens).  The KL term of
+ * Eq. 1 is dropped as in the paper (Section 3.1).  Rollouts are stored CSR-style
+ * twice: seq_offsets[N+1] gives each rollout's token range, group_offsets[B+1] each
+ * question's rollout range.  Readings: an empty rollout contributes 0; an empty group
+ * contributes 0 and still counts in the mean over questions.
+ * token_term_out [T] and seq_mean_out [N] are nullable.
+ */
+int e3o_grpo_objective(const float *logp_new, const float *logp_old, const int32_t *seq_offsets,
+                       const float *adv, const int32_t *group_offsets, int32_t num_groups,
+                       double clip_eps, double *token_term_out, double *seq_mean_out,
+                       double *objective_out)
+{
+    if (num_groups < 0 || !(clip_eps >= 0.0)) return -5;
+    double total = 0.0;
+    for (int32_t q = 0; q < num_groups; ++q) {
+        int32_t i0 = group_offsets[q], i1 = group_offsets[q + 1];
+        double group_sum = 0.0;
+        for (int32_t i = i0; i < i1; ++i) {
+            int64_t t0 = seq_offsets[i], t1 = seq_offsets[i + 1];
+            double A = (double)adv[i], seq_sum = 0.0;
+            for (int64_t t = t0; t < t1; ++t) {
+                double r = exp((double)logp_new[t] - (double)logp_old[t]);
+                double rc = r < 1.0 - clip_eps ? 1.0 - clip_eps : (r > 1.0 + clip_eps ? 1.0 + clip_eps : r);
+                double a = r * A, b = rc * A;
+                double term = a < b ? a : b;
+                if (token_term_out) token_term_out[t] = term;
+                seq_sum += term;
+            }
+            double seq_mean = t1 > t0 ? seq_sum / (double)(t1 - t0) : 0.0;
+            if (seq_mean_out) seq_mean_out[i] = seq_mean;
+            group_sum += seq_mean;
+        }
+        if (i1 > i0) total += group_sum / (double)(i1 - i0);
+    }
+    *objective_out = num_groups > 0 ? total / (double)num_groups : 0.0;
+    return 0;
+}

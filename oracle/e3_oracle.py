@@ -73,6 +73,8 @@ def _declare(L):
     L.e3o_logit_gaps.restype = C.c_int
     L.e3o_temperature_update_gap.argtypes = [f64, f64, f64, f64, i64, i64, i64, f64, f64, f64, vp, vp]
     L.e3o_temperature_update_gap.restype = C.c_int
+    L.e3o_grpo_objective.argtypes = [vp, vp, vp, vp, vp, i32, f64, vp, vp, vp]
+    L.e3o_grpo_objective.restype = C.c_int
     L.e3o_max_threads.argtypes = []
     L.e3o_max_threads.restype = C.c_int
 
@@ -275,6 +277,23 @@ def temperature_update_gap(tau_t: float, H_t: float, H_init: float, delta: float
     rc = lib().e3o_temperature_update_gap(tau_t, H_t, H_init, delta, t, t_anneal, t_max, eta,
                                           tau_min, tau_max, C.addressof(nxt), C.addressof(tgt))
     return rc, nxt.value, tgt.value
+
+
+def grpo_objective(logp_new, logp_old, seq_offsets, adv, group_offsets, clip_eps: float):
+    """Returns (J, token_terms float64 [T], seq_means float64 [N])."""
+    ln = np.ascontiguousarray(logp_new, dtype=np.float32)
+    lo = np.ascontiguousarray(logp_old, dtype=np.float32)
+    so = np.ascontiguousarray(seq_offsets, dtype=np.int32)
+    ad = np.ascontiguousarray(adv, dtype=np.float32)
+    go = np.ascontiguousarray(group_offsets, dtype=np.int32)
+    terms = np.full(ln.shape[0], np.nan)
+    means = np.full(ad.shape[0], np.nan)
+    J = C.c_double(float("nan"))
+    rc = lib().e3o_grpo_objective(_ptr(ln), _ptr(lo), _ptr(so), _ptr(ad), _ptr(go), go.shape[0] - 1,
+                                  clip_eps, _ptr(terms), _ptr(means), C.addressof(J))
+    if rc != 0:
+        raise RuntimeError(f"e3o_grpo_objective failed: {rc}")
+    return J.value, terms, means
 
 
 def max_threads() -> int:
