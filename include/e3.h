@@ -168,6 +168,31 @@ int e3_grpo_advantages(const float* rewards, const int32_t* group_offsets,
                        float* adv_out, void* hip_stream);
 
 /*
+ * Forward value of the GRPO objective, Eq. 1 without the KL term (which the paper
+ * drops, Section 3.1):
+ *   J = mean_q (1/G_q) sum_{i in q} (1/|o_i|) sum_t min( r A_i , clip(r, 1-eps, 1+eps) A_i ),
+ *   r = exp(logp_new[t] - logp_old[t]).
+ * logp_new, logp_old  [T] fp32: log-probs of the rollout tokens under the current and
+ *                     the sampling policy (e3_logprob_entropy / e3_sample_entropy).
+ * seq_offsets    [num_seqs + 1] int32: token range of each rollout (CSR).
+ * adv            [num_seqs] fp32: per-rollout advantage (e3_grpo_advantages).
+ * group_offsets  [num_groups + 1] int32: rollout range of each question (CSR; the
+ *                same array e3_grpo_advantages takes).  group_offsets[num_groups]
+ *                must equal num_seqs (caller's contract).
+ * clip_eps       >= 0 (E3_ERR_VALUE otherwise).
+ * token_term_out [T] fp32 or NULL: the per-token min(...) term.
+ * seq_mean_out   [num_seqs] fp64, required: per-rollout mean term (0 for an empty
+ *                rollout); also the staging buffer of the two-stage reduction.
+ * objective_out  one double (device), required.  An empty group contributes 0 and
+ *                still counts in the mean over questions; num_groups == 0 gives 0.
+ * Sums in fp64 in a fixed order.
+ */
+int e3_grpo_objective(const float* logp_new, const float* logp_old, const int32_t* seq_offsets,
+                      const float* adv, int32_t num_seqs, const int32_t* group_offsets,
+                      int32_t num_groups, float clip_eps, float* token_term_out,
+                      double* seq_mean_out, double* objective_out, void* hip_stream);
+
+/*
  * Temperature scheduler, host only (no GPU work, all pointers are HOST):
  *   H_target = H_init                                      for t < t_anneal or t_anneal < 0
  *            = H_init [eta + (1-eta)(1 + cos(pi x))/2]      otherwise (Eq. 5),

@@ -23,7 +23,7 @@ E3_TILE_CHUNK, E3_TILE_LANES, E3_TILE_DEPTH = 8, 64, 16
 EXPORTS = ("e3_strerror", "e3_workspace_bytes", "e3_sample_entropy", "e3_logprob_entropy",
            "e3_grpo_advantages", "e3_temperature_update", "e3_difficulty_ranks",
            "e3_allocate_budgets", "e3_budget_bounds", "e3_logprob_entropy_gap",
-           "e3_temperature_update_gap")
+           "e3_temperature_update_gap", "e3_grpo_objective")
 
 _lib: Optional[C.CDLL] = None
 
@@ -58,6 +58,8 @@ def lib() -> C.CDLL:
         L.e3_logprob_entropy_gap.restype = C.c_int
         L.e3_temperature_update_gap.argtypes = [f64, f64, f64, f64, i64, i64, i64, f64, f64, f64, vp, vp]
         L.e3_temperature_update_gap.restype = C.c_int
+        L.e3_grpo_objective.argtypes = [vp, vp, vp, vp, i32, vp, i32, f32, vp, vp, vp, vp]
+        L.e3_grpo_objective.restype = C.c_int
         L.e3_grpo_advantages.argtypes = [vp, vp, i32, i32, f32, vp, vp]
         L.e3_grpo_advantages.restype = C.c_int
         L.e3_temperature_update.argtypes = [f64, f64, f64, i64, i64, i64, i64, f64, f64, f64, vp, vp]
@@ -303,3 +305,29 @@ def e3_temperature_update_gap(tau_t: float, H_t: float, H_init: float, gap: floa
     if rc != E3_OK:
         raise E3Error(rc, "e3_temperature_update_gap")
     return nxt.value, tgt.value
+
+
+def e3_grpo_objective(logp_new: torch.Tensor, logp_old: torch.Tensor, seq_offsets: torch.Tensor,
+                      adv: torch.Tensor, group_offsets: torch.Tensor, clip_eps: float,
+                      want_token_terms: bool = False):
+    """Returns (objective fp64 [1], seq_mean fp64 [N], token_terms fp32 [T] or None), on the device."""
+    dev = logp_new.device
+    if not logp_new.is_cuda:
+        raise ValueError("logp_new must live on the GPU")
+    T = logp_new.shape[0]
+    N = adv.shape[0]
+    B = group_offsets.shape[0] - 1
+    _check(logp_new, torch.float32, T, "logp_new", dev)
+    _check(logp_old, torch.float32, T, "logp_old", dev)
+    _check(seq_offsets, torch.int32, N + 1, "seq_offsets", dev)
+    _check(adv, torch.float32, N, "adv", dev)
+    _check(group_offsets, torch.int32, B + 1, "group_offsets", dev)
+    terms = torch.empty(T, dtype=torch.float32, device=dev) if want_token_terms else None
+    seq_mean = torch.empty(N, dtype=torch.float64, device=dev)
+    J = torch.empty(1, dtype=torch.float64, device=dev)
+    rc = lib().e3_grpo_objective(_ptr(logp_new), _ptr(logp_old), _ptr(seq_offsets), _ptr(adv), N,
+                                 _ptr(group_offsets), B, float(clip_eps), _ptr(terms),
+                                 _ptr(seq_mean), _ptr(J), _stream(dev))
+    if rc != E3_OK:
+        raise E3Error(rc, "e3_grpo_objective")
+    return J, seq_mean, terms

@@ -142,3 +142,22 @@ extern "C" int e3_grpo_advantages(const float* rewards, const int32_t* group_off
                                                 adv_out, static_cast<hipStream_t>(hip_stream));
     return err == hipSuccess ? E3_OK : E3_ERR_LAUNCH;
 }
+
+extern "C" int e3_grpo_objective(const float* logp_new, const float* logp_old,
+                                 const int32_t* seq_offsets, const float* adv, int32_t num_seqs,
+                                 const int32_t* group_offsets, int32_t num_groups, float clip_eps,
+                                 float* token_term_out, double* seq_mean_out, double* objective_out,
+                                 void* hip_stream)
+{
+    if (num_seqs < 0 || num_groups < 0) return E3_ERR_SHAPE;
+    if (!(clip_eps >= 0.0f) || !std::isfinite(clip_eps)) return E3_ERR_VALUE;
+    if (objective_out == nullptr || group_offsets == nullptr) return E3_ERR_NULL;
+    if (num_seqs > 0 && (logp_new == nullptr || logp_old == nullptr || seq_offsets == nullptr ||
+                         adv == nullptr || seq_mean_out == nullptr))
+        return E3_ERR_NULL;
+    hipError_t err = e3::launch_grpo_objective(logp_new, logp_old, seq_offsets, adv, num_seqs,
+                                               group_offsets, num_groups, clip_eps, token_term_out,
+                                               seq_mean_out, objective_out,
+                                               static_cast<hipStream_t>(hip_stream));
+    return err == hipSuccess ? E3_OK : E3_ERR_LAUNCH;
+}

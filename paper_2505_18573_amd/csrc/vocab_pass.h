@@ -29,4 +29,10 @@ hipError_t launch_entropy_reduce(const float* entropy, const uint8_t* mask, int6
 hipError_t launch_grpo_advantages(const float* rewards, const int32_t* offsets, int32_t num_groups,
                                   int32_t ddof, float eps, float* adv_out, hipStream_t stream);
 
+hipError_t launch_grpo_objective(const float* logp_new, const float* logp_old,
+                                 const int32_t* seq_offsets, const float* adv, int32_t num_seqs,
+                                 const int32_t* group_offsets, int32_t num_groups, float clip_eps,
+                                 float* token_term_out, double* seq_mean_out, double* objective_out,
+                                 hipStream_t stream);
+
 }  // namespace e3
