@@ -79,7 +79,7 @@ __device__ __forceinline__ void finish_row(const VocabPassArgs& a, int64_t row,
 
     // R is the common reference, `peak` the largest logit of the row; the partial
     // that holds it is the lowest lane with that top, every other excluded maximum
-    // joins the rest as an ordinary term.  All in fp64 from here.
+    // joins the rest as an ordinary term.
     const float R = wave_max(p.rc);
     const float peak = wave_max(p.top);
     const unsigned long long holders = __ballot(p.top == peak);
@@ -88,6 +88,28 @@ __device__ __forceinline__ void finish_row(const VocabPassArgs& a, int64_t row,
     const double cd = (double)c;
     const double d = live ? (double)R - (double)p.rc : 0.0;       // integer >= 0
     const int sh = d > 4000.0 ? -4000 : -(int)d;
+
+    // Rollout side, level 1 across partials first (weights brought to the common
+    // reference by exact scaling), so that the columns of the winning tile are
+    // requested before the fp64 merge below and arrive while it runs.
+    float cz[4] = {kAbsent, kAbsent, kAbsent, kAbsent};
+    uint32_t w[4] = {0u, 0u, 0u, 0u};
+    int64_t col0 = 0;
+    if (kSample) {
+        const Cand win = wave_best(Cand{live ? ldexpf(p.q, sh) : -1.0f, p.tile});
+        const int wst = win.idx / kLanes, wslot = win.idx % kLanes;
+        // 32 lanes x 4 consecutive columns cover the tile
+        col0 = (int64_t)wst * kSuperCols + (int64_t)(lane >> 1) * kSweepCols
+             + (int64_t)wslot * kChunk + (lane & 1) * 4;
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+            if (lane < 32 && col0 + j < V) cz[j] = Chunk::load_one(rowp, col0 + j);
+        const uint64_t grow = a.row_base + (uint64_t)row;
+        philox4x32_10((uint32_t)(col0 >> 2), (uint32_t)grow, (uint32_t)(grow >> 32), 2u,
+                      (uint32_t)a.seed, (uint32_t)(a.seed >> 32), w);
+    }
+
+    // Row sums in fp64.
     double S_l = 0.0, W_l = 0.0;
     if (live) {
         S_l = ldexp(p.S, sh);
@@ -113,21 +135,8 @@ __device__ __forceinline__ void finish_row(const VocabPassArgs& a, int64_t row,
     int64_t tok;
     float z_tok;
     if (kSample) {
-        // level 1 across partials: weights brought to the common reference (exact scaling)
-        const Cand win = wave_best(Cand{live ? ldexpf(p.q, sh) : -1.0f, p.tile});
         // Level 2: Gumbel-max inside the winning tile, in race form: maximise
-        // 2^{(z - zmax) c} / E_col.  32 lanes x 4 consecutive columns cover the tile.
-        const int wst = win.idx / kLanes, wslot = win.idx % kLanes;
-        const int64_t col0 = (int64_t)wst * kSuperCols + (int64_t)(lane >> 1) * kSweepCols
-                           + (int64_t)wslot * kChunk + (lane & 1) * 4;
-        float cz[4];
-#pragma unroll
-        for (int j = 0; j < 4; ++j)
-            cz[j] = (lane < 32 && col0 + j < V) ? Chunk::load_one(rowp, col0 + j) : kAbsent;
-        const uint64_t grow = a.row_base + (uint64_t)row;
-        uint32_t w[4];
-        philox4x32_10((uint32_t)(col0 >> 2), (uint32_t)grow, (uint32_t)(grow >> 32), 2u,
-                      (uint32_t)a.seed, (uint32_t)(a.seed >> 32), w);
+        // 2^{(z - zmax) c} / E_col.
         const float zmax = wave_max(fmaxf(fmaxf(cz[0], cz[1]), fmaxf(cz[2], cz[3])));
         Cand cb{-1.0f, 0x7FFFFFFF};
 #pragma unroll
