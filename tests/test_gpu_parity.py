@@ -290,3 +290,36 @@ def test_many_short_rows():
     check_sample(lg, tau, 1.0, seed=6, row_base=0, label="6000 rows x 8712")
     tgt = torch.randint(0, 8712, (6000,), generator=g, device=DEV).to(torch.int32)
     check_logprob(lg, tgt, None, tau, 1.0, "6000 rows x 8712 logprob")
+
+
+def test_non_finite_inputs_give_nan_outputs_and_valid_tokens():
+    # documented behaviour: NaN / inf logits or tau <= 0 poison that row's outputs only
+    g = torch.Generator(device=DEV).manual_seed(13)
+    lg = (torch.randn((8, 20_000), generator=g, device=DEV) * 3).to(torch.bfloat16)
+    lg[1, 5] = float("nan")
+    lg[2, 19_999] = float("inf")
+    lg[3, 0] = float("-inf")
+    tau = torch.ones(8, device=DEV)
+    tau[5] = 0.0
+    tau[6] = -1.0
+    tok, logp, ent = e3.e3_sample_entropy(lg, tau, 1.0, seed=1, row_base=0)
+    torch.cuda.synchronize()
+    tok = tok.cpu().numpy()
+    assert ((tok >= 0) & (tok < 20_000)).all()
+    clean = [0, 4, 7]
+    ref = o.sample_entropy(wl.host_bits(lg[clean]), None, 1.0, 1, 0)
+    for j, r in enumerate(clean):                      # untouched rows are unaffected
+        sub = e3.e3_sample_entropy(lg[r:r + 1], None, 1.0, seed=1, row_base=r)
+        assert sub[0].item() == tok[r]
+        assert close(ent[r].item(), o.logprob_entropy(wl.host_bits(lg[r:r + 1]), None, None, None, 1.0).entropy[0])
+    assert torch.isnan(ent[1]) and torch.isnan(ent[5])
+
+
+@pytest.mark.parametrize("rows", [1, 2, 3, 17])
+def test_odd_row_counts_and_group_tails(rows):
+    # workgroups own two rows: an odd count leaves a half-filled last group
+    g = torch.Generator(device=DEV).manual_seed(14 + rows)
+    lg = (torch.randn((rows, 3 * 8192), generator=g, device=DEV) * 3).to(torch.bfloat16)   # no ragged tail
+    check_sample(lg, None, 1.1, seed=2, row_base=7, label=f"{rows} rows x 24576")
+    lg2 = (torch.randn((rows, 200), generator=g, device=DEV) * 3).float()                  # many rows per group
+    check_sample(lg2, None, 0.9, seed=2, row_base=7, label=f"{rows} rows x 200")
