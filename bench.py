@@ -40,7 +40,7 @@ BYTES_PER_ROW = V * 2 + 4 + 12
 # HBM bytes per launch of the sample kernel from rocprofv3 FETCH_SIZE + WRITE_SIZE, each scaled by
 # what the same counter reads for a device copy of known size (profiles/…hbm_traffic.txt).
 # Valid for the kernel as profiled; set to None when the kernel changes until re-measured.
-MEASURED_TRAFFIC_BYTES = 157_166_059
+MEASURED_TRAFFIC_BYTES = 157_166_151
 
 
 def main() -> int:
@@ -217,11 +217,21 @@ def cpu_baseline(batch, rewards, offsets):
         lp = o.logprob_entropy(bits, s.token, None, tau, 1.0, nthreads=threads)
         o.temperature_update(1.0, lp.entropy_mean, lp.entropy_mean, V)
     dt = time.perf_counter() - t0
+    # the same step on one thread, over the first 64 rows (8 groups)
+    n1 = 64
+    t0 = time.perf_counter()
+    s1 = o.sample_entropy(bits[:n1], tau[:n1], 1.0, 99, 0, nthreads=1)
+    o.grpo_advantages(r[:n1], off[:n1 // ROLLOUTS + 1])
+    o.logprob_entropy(bits[:n1], s1.token, None, tau[:n1], 1.0, nthreads=1)
+    dt1 = time.perf_counter() - t0
     return {
         "value": ROWS * reps / dt, "unit": "rows/s", "cores": threads, "kind": "oracle",
         "sample": f"{reps} full steps of the same 512-row batch ({ROWS * reps} rows), fp64, "
                   f"OpenMP over rows",
         "seconds": dt,
+        "logit_GBps": ROWS * reps * 2 * V * 2 / dt / 1e9,
+        "single_thread": {"value": n1 / dt1, "unit": "rows/s", "cores": 1,
+                          "sample": f"one step over the first {n1} rows", "seconds": dt1},
     }
 
 
