@@ -30,7 +30,7 @@ typedef enum {
     E3_ERR_DTYPE = -3,     /* dtype is not an e3_dtype */
     E3_ERR_ALIGN = -4,     /* logits base or row pitch not 16-byte aligned */
     E3_ERR_VALUE = -5,     /* a scalar is outside its domain (tau <= 0, H <= 0, ...) */
-    E3_ERR_WORKSPACE = -6, /* workspace missing or smaller than e3_workspace_bytes() */
+    E3_ERR_WORKSPACE = -6, /* reserved: the workspace is optional, no entry point returns this */
     E3_ERR_LAUNCH = -7     /* the HIP runtime refused a launch (see hipGetLastError) */
 } e3_status;
 
@@ -51,11 +51,18 @@ typedef enum { E3_F32 = 0, E3_BF16 = 1 } e3_dtype;
 const char* e3_strerror(int status);
 
 /*
- * Bytes of device workspace that e3_sample_entropy / e3_logprob_entropy need
- * for a [rows, V] problem (pure host function).  The present kernels stage all
- * partial results in LDS, so this returns 0 for every shape and `workspace` may
- * be NULL; the argument is kept so that callers size and pass it the same way
- * should a later version stage rows in device memory.
+ * Bytes of device workspace that e3_sample_entropy / e3_logprob_entropy can use
+ * for a [rows, V] problem (pure host function; 0 for rows > 1024, at most 2 MiB).
+ * The workspace is optional: with it, a small batch (too few rows to give every
+ * compute unit whole rows of its own) is cut into runs of columns that are streamed
+ * by many workgroups, their 32-byte partial results staged in the workspace and
+ * merged by a second launch on the same stream; without it, or when it is smaller
+ * than this bound or not 16-byte aligned, every row is streamed by one workgroup,
+ * which is correct for any shape but slow for small batches.  Both ways compute the
+ * same quantities; tokens can differ between them only on rows whose sampling race
+ * is decided within fp32 rounding (the rows the near-tie rule below exempts).
+ * The workspace holds no state between calls; calls that share one must be ordered
+ * (same stream) because the merge reads what the first launch wrote.
  */
 size_t e3_workspace_bytes(int64_t rows, int64_t V);
 
@@ -91,8 +98,8 @@ size_t e3_workspace_bytes(int64_t rows, int64_t V);
  *             not depend on how rows are batched.
  * token_out   [rows] int32;  logp_out, entropy_out [rows] fp32 (natural log).
  *             logp_out and entropy_out may be NULL.
- * workspace   device scratch of at least e3_workspace_bytes(rows, V) bytes
- *             (0 today, so NULL is accepted); never read when that is 0.
+ * workspace   device scratch of workspace_bytes bytes, or NULL (see
+ *             e3_workspace_bytes); contents on entry are ignored.
  * V           at most 2,080,768 columns (per-workgroup tables must fit LDS),
  *             else E3_ERR_SHAPE.
  * rows == 0 is a no-op.  fp32 accumulation per lane, fp64 merges.

@@ -122,7 +122,11 @@ def new_workspace(rows: int, V: int, device) -> Optional[torch.Tensor]:
     return torch.empty((need + 3) // 4, dtype=torch.int32, device=device)
 
 
-def _workspace(rows: int, V: int, workspace: Optional[torch.Tensor], device):
+def _workspace(rows: int, V: int, workspace, device):
+    """workspace: a tensor to use, None to allocate one of e3_workspace_bytes(), or False to
+    pass NULL (every row then stays in one workgroup)."""
+    if workspace is False:
+        return None, 0
     if workspace is None:
         workspace = new_workspace(rows, V, device)
     if workspace is None:
@@ -135,7 +139,7 @@ def e3_sample_entropy(logits: torch.Tensor, tau_rows: Optional[torch.Tensor], ta
                       token_out: Optional[torch.Tensor] = None,
                       logp_out: Optional[torch.Tensor] = None,
                       entropy_out: Optional[torch.Tensor] = None,
-                      workspace: Optional[torch.Tensor] = None):
+                      workspace=None):
     """Returns (token int32 [rows], logp fp32 [rows], entropy fp32 [rows])."""
     dt, rows, V, stride = _logits_meta(logits)
     dev = logits.device
@@ -166,7 +170,7 @@ def e3_logprob_entropy(logits: torch.Tensor, target_ids: Optional[torch.Tensor],
                        entropy_out: Optional[torch.Tensor] = None,
                        entropy_sum_out: Optional[torch.Tensor] = None,
                        entropy_count_out: Optional[torch.Tensor] = None,
-                       workspace: Optional[torch.Tensor] = None, want_sum: bool = True):
+                       workspace=None, want_sum: bool = True):
     """Returns (logp fp32 [rows] or None, entropy fp32 [rows], entropy_sum fp64 [1] or None,
     entropy_count int64 [1] or None); the sum and count stay on the device."""
     dt, rows, V, stride = _logits_meta(logits)
@@ -270,7 +274,7 @@ def e3_budget_bounds(G: int, passes_done: int, step: int, G_min_limit: int, G_ma
 
 def e3_logprob_entropy_gap(logits: torch.Tensor, target_ids: Optional[torch.Tensor],
                            row_mask: Optional[torch.Tensor], tau_rows: Optional[torch.Tensor],
-                           tau_scalar: float, workspace: Optional[torch.Tensor] = None):
+                           tau_scalar: float, workspace=None):
     """Returns (logp or None, entropy, gap, entropy_sum fp64 [1], gap_sum fp64 [1], count int64 [1]),
     all on the device."""
     dt, rows, V, stride = _logits_meta(logits)

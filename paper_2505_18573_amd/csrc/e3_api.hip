@@ -47,8 +47,7 @@ extern "C" const char* e3_strerror(int status)
 
 extern "C" size_t e3_workspace_bytes(int64_t rows, int64_t V)
 {
-    (void)rows; (void)V;
-    return 0;   // partial results are staged in LDS: no device workspace is needed
+    return e3::vocab_pass_workspace_bytes(rows, V);
 }
 
 extern "C" int e3_sample_entropy(const void* logits, int dtype, int64_t rows, int64_t V,
@@ -63,7 +62,6 @@ extern "C" int e3_sample_entropy(const void* logits, int dtype, int64_t rows, in
     if (rc != E3_OK) return rc;
     if (rows == 0) return E3_OK;
     if (token_out == nullptr) return E3_ERR_NULL;
-    (void)workspace; (void)workspace_bytes;
 
     e3::VocabPassArgs a{};
     a.logits = logits; a.rows = rows; a.V = V; a.row_stride = row_stride;
@@ -71,7 +69,7 @@ extern "C" int e3_sample_entropy(const void* logits, int dtype, int64_t rows, in
     a.seed = seed; a.row_base = row_base;
     a.target_ids = nullptr;
     a.token_out = token_out; a.logp_out = logp_out; a.entropy_out = entropy_out;
-    hipError_t err = e3::launch_vocab_pass(a, dtype == E3_BF16, true,
+    hipError_t err = e3::launch_vocab_pass(a, dtype == E3_BF16, true, workspace, workspace_bytes,
                                            static_cast<hipStream_t>(hip_stream));
     return err == hipSuccess ? E3_OK : E3_ERR_LAUNCH;
 }
@@ -91,7 +89,6 @@ extern "C" int e3_logprob_entropy_gap(const void* logits, int dtype, int64_t row
     if (rows > 0 && entropy_out == nullptr) return E3_ERR_NULL;
     if (logp_out != nullptr && target_ids == nullptr) return E3_ERR_NULL;
     if (gap_sum_out != nullptr && gap_out == nullptr) return E3_ERR_NULL;
-    (void)workspace; (void)workspace_bytes;
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
 
     if (rows > 0) {
@@ -101,7 +98,8 @@ extern "C" int e3_logprob_entropy_gap(const void* logits, int dtype, int64_t row
         a.target_ids = target_ids;
         a.token_out = nullptr; a.logp_out = logp_out; a.entropy_out = entropy_out;
         a.gap_out = gap_out;
-        if (e3::launch_vocab_pass(a, dtype == E3_BF16, false, stream) != hipSuccess)
+        if (e3::launch_vocab_pass(a, dtype == E3_BF16, false, workspace, workspace_bytes, stream)
+            != hipSuccess)
             return E3_ERR_LAUNCH;
     }
     // also for rows == 0: sums and count are then written as 0

@@ -24,6 +24,13 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 #ifndef E3_NT_LOADS
 #define E3_NT_LOADS 1        // stream the logits with non-temporal loads
 #endif
+#ifndef E3_ROUND_AWARE_ROWS
+#define E3_ROUND_AWARE_ROWS 1     // size row-block workgroups for whole rounds over the CUs
+#endif
+#ifndef E3_SPLIT_BELOW_NUM        // small-batch path while row-block workgroups <= CUs * NUM / DEN
+#define E3_SPLIT_BELOW_NUM 5
+#define E3_SPLIT_BELOW_DEN 8
+#endif
 
 constexpr int kChunk = 8;                       // columns per lane per sweep
 constexpr int kLanes = 64;                      // lanes = tiles per super-tile

@@ -18,7 +18,13 @@ struct VocabPassArgs {
     float* gap_out;                   // nullable: measured logit gap (Appendix A's Delta)
 };
 
-hipError_t launch_vocab_pass(const VocabPassArgs& a, bool is_bf16, bool sample, hipStream_t stream);
+// `workspace` (device, 16-byte aligned, nullable) lets small batches be cut across
+// many workgroups; without it, or when it is too small, whole rows stay in one workgroup.
+hipError_t launch_vocab_pass(const VocabPassArgs& a, bool is_bf16, bool sample,
+                             void* workspace, size_t workspace_bytes, hipStream_t stream);
+
+// upper bound of the workspace the small-batch path can use for this shape (0: none)
+size_t vocab_pass_workspace_bytes(int64_t rows, int64_t V);
 
 // false when V is so large that the per-workgroup tables do not fit LDS
 bool vocab_pass_fits(int64_t V);

@@ -53,11 +53,12 @@ __host__ __device__ inline size_t lds_bytes(int rpb, int nst, bool sample)
          + (sample ? (size_t)rpb * nst * kLanes * sizeof(float) : 0);
 }
 
-// Row epilogue, run by the wave that delivered the row's last item: merge the partials
-// (one per lane), level 2 of the sampler or the target gather, outputs.
-template <typename Chunk, bool kSample, int kWaves>
+// Row epilogue, run by one wave once all of the row's partials are written: merge the
+// partials (one per lane, nparts <= 64), level 2 of the sampler or the target gather,
+// outputs.
+template <typename Chunk, bool kSample>
 __device__ __forceinline__ void finish_row(const VocabPassArgs& a, int64_t row,
-                                           const RowPartial* parts, int lane)
+                                           const RowPartial* parts, int nparts, int lane)
 {
     const int64_t V = a.V;
     const char* rowp = static_cast<const char*>(a.logits)
@@ -75,7 +76,7 @@ __device__ __forceinline__ void finish_row(const VocabPassArgs& a, int64_t row,
 
     RowPartial p;
     p.S = 0.0; p.W = 0.0; p.rc = -INFINITY; p.top = -INFINITY; p.q = -1.0f; p.tile = 0;
-    if (lane <= kWaves) p = parts[lane];
+    if (lane < nparts) p = parts[lane];
 
     // R is the common reference, `peak` the largest logit of the row; the partial
     // that holds it is the lowest lane with that top, every other excluded maximum
@@ -175,6 +176,51 @@ __device__ __forceinline__ void finish_row(const VocabPassArgs& a, int64_t row,
     }
 }
 
+__device__ __forceinline__ void fresh(LaneState& s)
+{
+    s.rc = -INFINITY; s.top = -INFINITY; s.dom_lane = 0; s.dom_open = false;
+    s.S = s.W = s.sT0 = s.sT1 = s.wT0 = s.wT1 = 0.0f;
+    s.best = Cand{-1.0f, 0};
+}
+
+// A row's incomplete last super-tile: sweeps in two halves of 8, the guarded loads of a
+// half all issued before the first is used; columns past V count as absent.  Returns
+// whether this lane's tile holds any column.
+template <typename Chunk>
+__device__ __forceinline__ bool stream_ragged(LaneState& s, const char* rowp, int64_t cbase,
+                                              int64_t lane_col, int64_t V, float c, int lane)
+{
+    bool any_valid = false;
+#pragma unroll 1
+    for (int half = 0; half < 2; ++half) {
+        const int64_t hbase = cbase + (int64_t)half * (kDepth / 2) * kSweepCols;
+        if (hbase - lane_col >= V) break;            // uniform: nothing left
+        Chunk rb[kDepth / 2];
+#pragma unroll
+        for (int i = 0; i < kDepth / 2; ++i)
+            if (hbase + i * kSweepCols + kChunk <= V) rb[i].load(rowp, hbase + i * kSweepCols);
+#pragma unroll
+        for (int i = 0; i < kDepth / 2; ++i) {
+            const int64_t col = hbase + i * kSweepCols;
+            float z[8];
+            bool valid = false;
+            if (col + kChunk <= V) {
+                rb[i].unpack(z);
+                valid = true;
+            } else {
+#pragma unroll
+                for (int j = 0; j < 8; ++j) {
+                    z[j] = kAbsent;
+                    if (col + j < V) { z[j] = Chunk::load_one(rowp, col + j); valid = true; }
+                }
+            }
+            any_valid |= valid;
+            if (__any(valid)) accumulate_chunk(s, z, c, lane);
+        }
+    }
+    return any_valid;
+}
+
 template <typename Chunk, bool kSample, int kWaves, int kAhead>
 __global__ __launch_bounds__(kWaves * 64)
 void vocab_pass_kernel(VocabPassArgs a, int rpb)
@@ -255,11 +301,6 @@ void vocab_pass_kernel(VocabPassArgs a, int rpb)
         if (lane == 0) t = atomicAdd(&hdr->ticket, 1u);
         return kWaves + (int)__builtin_amdgcn_readfirstlane(t);
     };
-    auto fresh = [&](LaneState& s) {
-        s.rc = -INFINITY; s.top = -INFINITY; s.dom_lane = 0; s.dom_open = false;
-        s.S = s.W = s.sT0 = s.sT1 = s.wT0 = s.wT1 = 0.0f;
-        s.best = Cand{-1.0f, 0};
-    };
     // Hand over what this wave holds for local row r (n_items of its items); the wave
     // that brings the row's count to nst finishes the row.
     auto deliver = [&](LaneState& s, int r, int slot, int n_items) {
@@ -275,7 +316,7 @@ void vocab_pass_kernel(VocabPassArgs a, int rpb)
         }
         before = __builtin_amdgcn_readfirstlane(before);
         if ((int)before + n_items == nst)
-            finish_row<Chunk, kSample, kWaves>(a, row0 + r, parts + r * (kWaves + 1), lane);
+            finish_row<Chunk, kSample>(a, row0 + r, parts + r * (kWaves + 1), kWaves + 1, lane);
     };
     auto row_scale = [&](int r) -> float {
         const float tau = a.tau_rows ? a.tau_rows[row0 + r] : a.tau_scalar;
@@ -283,8 +324,7 @@ void vocab_pass_kernel(VocabPassArgs a, int rpb)
     };
 
     // Incomplete super-tiles come first in the item order, so a wave meets them before it
-    // enters the pipelined loop: sweeps in two halves of 8, guarded loads of a half all
-    // issued before the first is used.
+    // enters the pipelined loop.
     while (have && item < n_ragged) {
         const int next = take_ticket();
         const int r = item, st = nfull;
@@ -293,35 +333,8 @@ void vocab_pass_kernel(VocabPassArgs a, int rpb)
         const float inv_e = kSample ? inv_e_tab[((size_t)r * nst + st) * kLanes + lane] : 0.0f;
         LaneState s;
         fresh(s);
-        const int64_t cbase = (int64_t)st * kSuperCols + lane_col;
-        bool any_valid = false;
-#pragma unroll 1
-        for (int half = 0; half < 2; ++half) {
-            const int64_t hbase = cbase + (int64_t)half * (kDepth / 2) * kSweepCols;
-            if (hbase - lane_col >= V) break;            // uniform: nothing left
-            Chunk rb[kDepth / 2];
-#pragma unroll
-            for (int i = 0; i < kDepth / 2; ++i)
-                if (hbase + i * kSweepCols + kChunk <= V) rb[i].load(rowp, hbase + i * kSweepCols);
-#pragma unroll
-            for (int i = 0; i < kDepth / 2; ++i) {
-                const int64_t col = hbase + i * kSweepCols;
-                float z[8];
-                bool valid = false;
-                if (col + kChunk <= V) {
-                    rb[i].unpack(z);
-                    valid = true;
-                } else {
-#pragma unroll
-                    for (int j = 0; j < 8; ++j) {
-                        z[j] = kAbsent;
-                        if (col + j < V) { z[j] = Chunk::load_one(rowp, col + j); valid = true; }
-                    }
-                }
-                any_valid |= valid;
-                if (__any(valid)) accumulate_chunk(s, z, c, lane);
-            }
-        }
+        const bool any_valid = stream_ragged<Chunk>(s, rowp, (int64_t)st * kSuperCols + lane_col,
+                                                    lane_col, V, c, lane);
         close_tile<kSample>(s, st * kLanes + lane, inv_e, any_valid, c, lane);
         deliver(s, r, kWaves, 1);
         item = next;
@@ -396,6 +409,90 @@ void vocab_pass_kernel(VocabPassArgs a, int rpb)
 }
 
 // ---------------------------------------------------------------------------
+// Small batches.  When the rows are too few to give every compute unit a workgroup
+// of whole rows, a row is cut into `nslots` runs of consecutive super-tiles and
+// every run gets a one-wave workgroup of its own, so that all of the chip's memory
+// channels are busy even for a single row.  A wave requests a whole super-tile (16
+// sweeps) at once, refills each register with the same sweep of its next super-tile
+// as soon as it has consumed it, draws the level-1 noise of its own tiles while the
+// loads are in flight, and writes one RowPartial to the workspace.  A second launch
+// of one wave per row merges a row's partials exactly as the row-block kernel's
+// epilogue does.
+// ---------------------------------------------------------------------------
+template <typename Chunk, bool kSample>
+__global__ __launch_bounds__(64)
+void vocab_split_kernel(VocabPassArgs a, RowPartial* __restrict__ ws, int nslots)
+{
+    const int lane = threadIdx.x;
+    const int64_t V = a.V;
+    const int nst = (int)((V + kSuperCols - 1) / kSuperCols);
+    const int nfull = (int)(V / kSuperCols);
+    const int64_t row = (int64_t)blockIdx.x / nslots;
+    const int slot = (int)((int64_t)blockIdx.x - row * nslots);
+    const int st_begin = slot * nst / nslots;        // runs differ by at most one super-tile
+    const int st_end = (slot + 1) * nst / nslots;
+
+    const char* rowp = static_cast<const char*>(a.logits) + row * a.row_stride * (int64_t)Chunk::kElemBytes;
+    const int64_t lane_col = (int64_t)lane * kChunk;
+
+    Chunk buf[kDepth];
+    if (st_begin < nfull) {
+        const int64_t b0 = (int64_t)st_begin * kSuperCols + lane_col;
+#pragma unroll
+        for (int i = 0; i < kDepth; ++i) buf[i].load(rowp, b0 + i * kSweepCols);
+    }
+    const float tau = a.tau_rows ? a.tau_rows[row] : a.tau_scalar;
+    const float c = kLog2eF / tau;
+    const uint64_t grow = a.row_base + (uint64_t)row;
+
+    LaneState s;
+    fresh(s);
+    for (int st = st_begin; st < st_end; ++st) {
+        const int tile = st * kLanes + lane;
+        float inv_e = 0.0f;
+        if (kSample) {
+            uint32_t w[4];
+            philox4x32_10((uint32_t)(tile >> 2), (uint32_t)grow, (uint32_t)(grow >> 32), 1u,
+                          (uint32_t)a.seed, (uint32_t)(a.seed >> 32), w);
+            const int k = tile & 3;
+            inv_e = 1.0f / exp_variate(k == 0 ? w[0] : k == 1 ? w[1] : k == 2 ? w[2] : w[3]);
+        }
+        if (st < nfull) {
+            const bool refill = st + 1 < st_end && st + 1 < nfull;     // uniform
+            const int64_t nb = (int64_t)(st + 1) * kSuperCols + lane_col;
+#pragma unroll
+            for (int i = 0; i < kDepth; ++i) {
+                float z[8];
+                buf[i].unpack(z);
+                if (refill) buf[i].load(rowp, nb + i * kSweepCols);
+                accumulate_chunk(s, z, c, lane);
+            }
+            close_tile<kSample>(s, tile, inv_e, true, c, lane);
+        } else {
+            const bool any_valid = stream_ragged<Chunk>(s, rowp, (int64_t)st * kSuperCols + lane_col,
+                                                        lane_col, V, c, lane);
+            close_tile<kSample>(s, tile, inv_e, any_valid, c, lane);
+        }
+    }
+    const double Sw = wave_sum((double)s.S);
+    const double Ww = wave_sum((double)s.W);
+    const Cand wb = kSample ? wave_best(s.best) : Cand{-1.0f, 0};
+    if (lane == 0) {
+        RowPartial p;
+        p.S = Sw; p.W = Ww; p.rc = s.rc; p.top = s.top; p.q = wb.q; p.tile = wb.idx;
+        ws[(size_t)blockIdx.x] = p;
+    }
+}
+
+template <typename Chunk, bool kSample>
+__global__ __launch_bounds__(64)
+void row_finish_kernel(VocabPassArgs a, const RowPartial* __restrict__ ws, int nslots)
+{
+    finish_row<Chunk, kSample>(a, (int64_t)blockIdx.x, ws + (size_t)blockIdx.x * nslots, nslots,
+                               (int)threadIdx.x);
+}
+
+// ---------------------------------------------------------------------------
 // Batch entropy sum for the scheduler's H_t (mean entropy of the current step,
 // Eq. 4): one workgroup, fp64, fixed summation order.
 // ---------------------------------------------------------------------------
@@ -430,20 +527,34 @@ void entropy_reduce_kernel(const float* __restrict__ entropy, const uint8_t* __r
 // ---------------------------------------------------------------------------
 constexpr size_t kLdsBudget = 64 * 1024;
 
-// Rows per workgroup: enough items that the ticket queue can balance the waves (two
-// per wave), at least two rows, and the noise table must fit LDS.  0 = does not fit.
+// Rows per workgroup.  At least enough items that the ticket queue can balance the
+// waves (two per wave), at least two rows, and the noise table must fit LDS
+// (0 = does not fit).  Beyond that minimum, a workgroup of this size occupies a compute
+// unit alone, so the launch runs in ceil(groups / CUs) rounds of rpb rows each: among
+// the sizes that fit, take the one with the fewest row-rounds (768 rows on 256 CUs:
+// 3 rows in one round instead of 2 rows in two), and on a tie the smallest (measured:
+// consecutive rounds of small workgroups overlap their ends and starts on a compute
+// unit, one long round does not).
 template <int kWaves>
-static int rows_per_group(int64_t V, bool sample)
+static int rows_per_group(int64_t rows, int64_t V, bool sample, int cus)
 {
     const int nst = (int)((V + kSuperCols - 1) / kSuperCols);
     int rpb = (2 * kWaves + nst - 1) / nst;
     if (rpb < 2) rpb = 2;
     while (rpb > 1 && lds_bytes<kWaves>(rpb, nst, sample) > kLdsBudget) --rpb;
     if (lds_bytes<kWaves>(rpb, nst, sample) > kLdsBudget) return 0;
+#if E3_ROUND_AWARE_ROWS
+    if (kWaves != 8) return rpb;      // smaller workgroups share a compute unit: no rounds
+    auto cost = [&](int r) { return ((rows + r - 1) / r + cus - 1) / cus * r; };
+    int best = rpb;
+    for (int r = rpb + 1; r <= 4 * rpb && lds_bytes<kWaves>(r, nst, sample) <= kLdsBudget; ++r)
+        if (cost(r) < cost(best)) best = r;
+    rpb = best;
+#endif
     return rpb;
 }
 
-bool vocab_pass_fits(int64_t V) { return rows_per_group<8>(V, true) > 0 && rows_per_group<4>(V, true) > 0; }
+bool vocab_pass_fits(int64_t V) { return rows_per_group<8>(1, V, true, 1) > 0 && rows_per_group<4>(1, V, true, 1) > 0; }
 
 static int compute_units()
 {
@@ -461,7 +572,7 @@ static int compute_units()
 template <typename Chunk, bool kSample, int kWaves>
 static hipError_t launch_groups(const VocabPassArgs& a, hipStream_t stream)
 {
-    const int rpb = rows_per_group<kWaves>(a.V, kSample);
+    const int rpb = rows_per_group<kWaves>(a.rows, a.V, kSample, compute_units());
     if (rpb == 0) return hipErrorInvalidValue;
     const int nst = (int)((a.V + kSuperCols - 1) / kSuperCols);
     const size_t lds = lds_bytes<kWaves>(rpb, nst, kSample);
@@ -482,16 +593,76 @@ static hipError_t launch_for(const VocabPassArgs& a, hipStream_t stream)
 #ifdef E3_FORCE_WAVES
     return launch_groups<Chunk, kSample, E3_FORCE_WAVES>(a, stream);
 #else
-    const int rpb8 = rows_per_group<8>(a.V, kSample);
+    const int rpb8 = rows_per_group<8>(1, a.V, kSample, 1);       // the minimum size
     if (rpb8 > 0 && (a.rows + rpb8 - 1) / rpb8 <= 4 * (int64_t)compute_units())
         return launch_groups<Chunk, kSample, 8>(a, stream);
     return launch_groups<Chunk, kSample, 4>(a, stream);
 #endif
 }
 
-hipError_t launch_vocab_pass(const VocabPassArgs& a, bool is_bf16, bool sample, hipStream_t stream)
+// Split path: used when the row-block path would leave compute units without a
+// workgroup and the caller brought enough workspace.  Every super-tile gets a wave of
+// its own (measured on MI355X: one-wave workgroups beyond what is resident are handed
+// out by the hardware dispatcher as earlier ones finish, which balances better than
+// longer static runs), except that a row has at most 64 runs: one partial per lane
+// of the merging wave.
+constexpr int64_t kSplitMaxRows = 1024;          // bound used by the workspace size
+
+struct SplitPlan {
+    int nslots;      // runs per row, 1 <= nslots <= min(64, super-tiles per row)
+};
+
+static SplitPlan split_plan(int64_t V)
+{
+    const int nst = (int)((V + kSuperCols - 1) / kSuperCols);
+    SplitPlan p;
+    p.nslots = nst < 64 ? nst : 64;
+    return p;
+}
+
+size_t vocab_pass_workspace_bytes(int64_t rows, int64_t V)
+{
+    if (rows <= 0 || rows > kSplitMaxRows || V <= 0) return 0;
+    const int64_t nst = (V + kSuperCols - 1) / kSuperCols;
+    return (size_t)rows * (size_t)(nst < 64 ? nst : 64) * sizeof(RowPartial);
+}
+
+template <typename Chunk, bool kSample>
+static hipError_t launch_split(const VocabPassArgs& a, RowPartial* ws, SplitPlan plan, hipStream_t stream)
+{
+    const unsigned blocks = (unsigned)(a.rows * plan.nslots);
+    hipLaunchKernelGGL((vocab_split_kernel<Chunk, kSample>), dim3(blocks), dim3(64), 0, stream,
+                       a, ws, plan.nslots);
+    hipError_t err = hipGetLastError();
+    if (err != hipSuccess) return err;
+    hipLaunchKernelGGL((row_finish_kernel<Chunk, kSample>), dim3((unsigned)a.rows), dim3(64), 0, stream,
+                       a, ws, plan.nslots);
+    return hipGetLastError();
+}
+
+hipError_t launch_vocab_pass(const VocabPassArgs& a, bool is_bf16, bool sample,
+                             void* workspace, size_t workspace_bytes, hipStream_t stream)
 {
     if (a.rows == 0) return hipSuccess;
+    const int cus = compute_units();
+    const int rpb8 = rows_per_group<8>(1, a.V, sample, 1);            // the minimum size
+#ifdef E3_SPLIT_ALWAYS
+    const bool few = a.rows <= kSplitMaxRows;
+#else
+    const bool few = a.rows <= kSplitMaxRows && rpb8 > 0
+                  && (a.rows + rpb8 - 1) / rpb8 * E3_SPLIT_BELOW_DEN <= (int64_t)cus * E3_SPLIT_BELOW_NUM;
+#endif
+    if (few && workspace != nullptr && (reinterpret_cast<uintptr_t>(workspace) & 15u) == 0) {
+        const SplitPlan plan = split_plan(a.V);
+        if ((size_t)a.rows * plan.nslots * sizeof(RowPartial) <= workspace_bytes) {
+            RowPartial* ws = static_cast<RowPartial*>(workspace);
+            if (is_bf16)
+                return sample ? launch_split<ChunkBf16, true>(a, ws, plan, stream)
+                              : launch_split<ChunkBf16, false>(a, ws, plan, stream);
+            return sample ? launch_split<ChunkF32, true>(a, ws, plan, stream)
+                          : launch_split<ChunkF32, false>(a, ws, plan, stream);
+        }
+    }
     if (is_bf16)
         return sample ? launch_for<ChunkBf16, true>(a, stream)
                       : launch_for<ChunkBf16, false>(a, stream);

@@ -42,7 +42,11 @@ def test_strerror_and_workspace():
         assert e3.e3_strerror(code) not in ("ok", "unknown status")
     assert e3.e3_strerror(-99) == "unknown status"
     assert e3.e3_workspace_bytes(0, 1) == 0
-    assert e3.e3_workspace_bytes(512, 151_936) == 0          # partials live in LDS
+    # 32 bytes per run of columns, at most one run per super-tile of 8192 columns and 64 per row
+    assert e3.e3_workspace_bytes(512, 151_936) == 512 * 19 * 32
+    assert e3.e3_workspace_bytes(3, 1024) == 3 * 1 * 32
+    assert e3.e3_workspace_bytes(1024, 2_000_000) == 1024 * 64 * 32
+    assert e3.e3_workspace_bytes(1025, 151_936) == 0         # large batches need none
 
 
 def _sample(logits=0x1000, dtype=1, rows=4, V=64, stride=64, tau_rows=None, tau=1.0,

@@ -49,12 +49,20 @@ def assert_close(x, ref, what):
 
 
 def check_sample(logits, tau_rows, tau_scalar, seed, row_base, label):
-    """Run both sides on `logits` (device tensor); assert parity; return stats."""
-    tok, logp, ent = e3.e3_sample_entropy(logits, tau_rows, tau_scalar, seed, row_base)
-    torch.cuda.synchronize()
+    """Run both sides on `logits` (device tensor); assert parity; return stats.  The
+    library runs twice: with a workspace (small batches are then cut across workgroups)
+    and without (whole rows per workgroup); both must match the oracle."""
     ref = o.sample_entropy(wl.host_bits(logits),
                            None if tau_rows is None else tau_rows.cpu().numpy(),
                            tau_scalar, seed, row_base, nthreads=NT)
+    _check_sample_against(ref, logits, tau_rows, tau_scalar, seed, row_base, label + " [no ws]", False)
+    return _check_sample_against(ref, logits, tau_rows, tau_scalar, seed, row_base, label, None)
+
+
+def _check_sample_against(ref, logits, tau_rows, tau_scalar, seed, row_base, label, workspace):
+    tok, logp, ent = e3.e3_sample_entropy(logits, tau_rows, tau_scalar, seed, row_base,
+                                          workspace=workspace)
+    torch.cuda.synchronize()
     tok = tok.cpu().numpy()
     assert ((tok >= 0) & (tok < logits.shape[1])).all()
     diff = tok != ref.token
@@ -76,13 +84,23 @@ def check_sample(logits, tau_rows, tau_scalar, seed, row_base, label):
 
 
 def check_logprob(logits, targets, mask, tau_rows, tau_scalar, label, rows_subset=None):
-    logp, ent, s, n = e3.e3_logprob_entropy(logits, targets, mask, tau_rows, tau_scalar)
-    torch.cuda.synchronize()
     sel = slice(None) if rows_subset is None else rows_subset
     sub = logits if rows_subset is None else logits[torch.as_tensor(rows_subset, device=logits.device)]
     pick = (lambda t: None if t is None else t.cpu().numpy()[sel])
     ref = o.logprob_entropy(wl.host_bits(sub), pick(targets), pick(mask), pick(tau_rows),
                             tau_scalar, nthreads=NT)
+    if e3.e3_workspace_bytes(logits.shape[0], logits.shape[1]) > 0:
+        _check_logprob_against(ref, sel, rows_subset, logits, targets, mask, tau_rows, tau_scalar,
+                               label + " [no ws]", False)
+    return _check_logprob_against(ref, sel, rows_subset, logits, targets, mask, tau_rows, tau_scalar,
+                                  label, None)
+
+
+def _check_logprob_against(ref, sel, rows_subset, logits, targets, mask, tau_rows, tau_scalar, label,
+                           workspace):
+    logp, ent, s, n = e3.e3_logprob_entropy(logits, targets, mask, tau_rows, tau_scalar,
+                                            workspace=workspace)
+    torch.cuda.synchronize()
     assert_close(ent.cpu().numpy()[sel], ref.entropy, f"{label} entropy")
     if targets is not None:
         got = logp.cpu().numpy()[sel]
