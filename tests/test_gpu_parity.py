@@ -341,3 +341,36 @@ def test_odd_row_counts_and_group_tails(rows):
     check_sample(lg, None, 1.1, seed=2, row_base=7, label=f"{rows} rows x 24576")
     lg2 = (torch.randn((rows, 200), generator=g, device=DEV) * 3).float()                  # many rows per group
     check_sample(lg2, None, 0.9, seed=2, row_base=7, label=f"{rows} rows x 200")
+
+
+# ------------------------------------------- small-batch path (workspace) specifics
+def test_wide_rows_more_super_tiles_than_lanes():
+    # 71 super-tiles: the small-batch path caps a row at 64 runs, so some waves stream two
+    V = 70 * 8192 + 104
+    g = torch.Generator(device=DEV).manual_seed(21)
+    lg = (torch.randn((3, V), generator=g, device=DEV) * 3).to(torch.bfloat16)
+    assert e3.e3_workspace_bytes(3, V) == 3 * 64 * 32
+    check_sample(lg, None, 0.8, seed=4, row_base=1 << 40, label="71 super-tiles")
+    tgt = torch.tensor([0, V - 1, 8192 * 64 + 5], dtype=torch.int32, device=DEV)
+    check_logprob(lg, tgt, None, None, 0.8, "71 super-tiles logprob")
+
+
+def test_unusable_workspace_falls_back_to_whole_rows():
+    g = torch.Generator(device=DEV).manual_seed(22)
+    lg = (torch.randn((5, 30_000), generator=g, device=DEV) * 3).to(torch.bfloat16)
+    want = e3.e3_sample_entropy(lg, None, 1.0, 9, 0, workspace=False)
+    need = e3.e3_workspace_bytes(5, 30_000)
+    small = torch.empty(need // 4 - 1, dtype=torch.int32, device=DEV)          # 4 bytes short
+    skew = torch.empty(need // 4 + 4, dtype=torch.int32, device=DEV)[1:]       # not 16-byte aligned
+    for ws in (small, skew):
+        got = e3.e3_sample_entropy(lg, None, 1.0, 9, 0, workspace=ws)
+        for a, b in zip(got, want):
+            assert torch.equal(a, b)                                           # same kernel, same bits
+    # a workspace that fits is used, reused across calls, and needs no initialisation
+    ws = torch.full((need // 4,), -1, dtype=torch.int32, device=DEV)
+    first = e3.e3_sample_entropy(lg, None, 1.0, 9, 0, workspace=ws)
+    again = e3.e3_sample_entropy(lg, None, 1.0, 9, 0, workspace=ws)
+    for a, b in zip(first, again):
+        assert torch.equal(a, b)
+    assert torch.equal(first[0], want[0])
+    assert torch.allclose(first[2], want[2], rtol=1e-5, atol=0)
