@@ -383,6 +383,144 @@ double e3o_entropy_target(double H_init, int64_t t, int64_t t_anneal, int64_t t_
     return H_init * (eta + (1.0 - eta) * 0.5 * (1.0 + cos(pi * x)));
 }
 
+
+/* ------------------------------------------------------------------------ */
+/* Restricted sampling: top-k and top-p (nucleus) truncation before the draw.  */
+/* The paper samples its rollouts unrestricted (Section 5.1, temperature 1);   */
+/* rollout engines usually offer both truncations, so this is the library's    */
+/* definition, stated on value levels so that it does not depend on how equal  */
+/* logits happen to be ordered:                                                */
+/*   * a LEVEL is the set of columns that store one bit pattern; levels are    */
+/*     ranked by stored value, highest first (-0 ranks just below +0);         */
+/*     level j has n_j columns, value z_j and weight w_j = exp((z_j - z_1)/tau) */
+/*   * C_j = n_1 + .. + n_j,  M_j = n_1 w_1 + .. + n_j w_j  (in that order)     */
+/*   * top-k (k >= 1):  j_k = first j with C_j >= k  (ties at the cut are kept; */
+/*     k = 0 or k >= V: all levels)                                            */
+/*   * top-p (p < 1), applied to the distribution renormalised over the top-k  */
+/*     levels:  j_p = first j <= j_k with M_j >= p M_{j_k};  p >= 1: j_p = j_k  */
+/*   * the kept set is levels 1..j_p; the draw is a Gumbel-max in two steps:    */
+/*       level:  argmax_j  ln(n_j w_j) + g_j, written as the race               */
+/*               argmax_j n_j w_j / E_j with E_j = -ln u_j; u_j from stream 3,  */
+/*               index = the level's stored bit pattern; ties to the higher level */
+/*       column: the columns of a level are equally likely: with u from stream  */
+/*               4, index 0, pos = floor(u n) = ((2k+1) n) >> 24 for            */
+/*               u = (k + 1/2) 2^-23, and the token is the pos-th column of the */
+/*               level in increasing column order                               */
+/*   * logp = (z_tok - z_1)/tau - ln M_{j_p}  (log-probability under the        */
+/*     truncated, renormalised distribution); kept = C_{j_p}.                   */
+/* near_cut marks rows whose top-p threshold lies within 1e-9 (relative) of a   */
+/* cumulative mass, near_tie rows whose two best race scores lie within 1e-5:   */
+/* both are exempt from exact parity.                                           */
+/* ------------------------------------------------------------------------ */
+typedef struct { uint32_t ord; uint32_t bits; int32_t col; } level_item;
+
+static int cmp_level_item(const void *pa, const void *pb)
+{
+    const level_item *a = (const level_item *)pa, *b = (const level_item *)pb;
+    if (a->ord != b->ord) return a->ord > b->ord ? -1 : 1;      /* higher value first */
+    return a->col < b->col ? -1 : (a->col > b->col ? 1 : 0);
+}
+
+/* monotone map of a binary32 pattern to an unsigned integer (value order, -0 < +0) */
+static uint32_t order_key(uint32_t f32bits)
+{
+    return (f32bits & 0x80000000u) ? ~f32bits : (f32bits | 0x80000000u);
+}
+
+int e3o_sample_restricted(const void *logits, int dtype, int64_t rows, int64_t V, int64_t row_stride,
+                          const float *tau_rows, float tau_scalar, int32_t top_k, double top_p,
+                          uint64_t seed, uint64_t row_base,
+                          int32_t *token_out, double *logp_out, int32_t *kept_out,
+                          uint8_t *near_tie_out, uint8_t *near_cut_out, int nthreads)
+{
+    if (!logits || rows < 0 || V < 1 || V > 0x7fffffff || (row_stride < V && row_stride != 0) ||
+        top_k < 0 || !(top_p > 0.0))
+        return -1;
+    size_t esz = dtype == E3O_F32 ? 4 : 2;
+    int failed = 0;
+    if (nthreads < 1) nthreads = 1;
+#pragma omp parallel for num_threads(nthreads) schedule(dynamic, 1)
+    for (int64_t r = 0; r < rows; ++r) {
+        level_item *it = (level_item *)malloc((size_t)V * sizeof(level_item));
+        int64_t *lv_first = (int64_t *)malloc((size_t)V * sizeof(int64_t));   /* first item of level j */
+        double *lv_M = (double *)malloc((size_t)V * sizeof(double));
+        if (!it || !lv_first || !lv_M) {
+#pragma omp atomic write
+            failed = 1;
+            free(it); free(lv_first); free(lv_M);
+            continue;
+        }
+        const void *row = (const char *)logits + (size_t)r * (size_t)row_stride * esz;
+        double tau = row_tau(tau_rows, tau_scalar, r);
+        uint64_t grow = row_base + (uint64_t)r;
+        for (int64_t i = 0; i < V; ++i) {
+            uint32_t stored, as32;
+            if (dtype == E3O_F32) { stored = ((const uint32_t *)row)[i]; as32 = stored; }
+            else { stored = ((const uint16_t *)row)[i]; as32 = stored << 16; }
+            it[i].ord = order_key(as32);
+            it[i].bits = stored;
+            it[i].col = (int32_t)i;
+        }
+        qsort(it, (size_t)V, sizeof(level_item), cmp_level_item);
+
+        /* levels, cumulative counts and masses in rank order */
+        double z1 = load_logit(row, dtype, (size_t)it[0].col);
+        int64_t nlev = 0;
+        double M = 0.0;
+        for (int64_t i = 0; i < V; ) {
+            int64_t e = i;
+            while (e < V && it[e].ord == it[i].ord) ++e;
+            double z = load_logit(row, dtype, (size_t)it[i].col);
+            M += (double)(e - i) * exp((z - z1) / tau);
+            lv_first[nlev] = i;
+            lv_M[nlev] = M;
+            ++nlev;
+            i = e;
+        }
+        #define LV_END(j) ((j) + 1 < nlev ? lv_first[(j) + 1] : V)     /* C_j */
+        int64_t jk = nlev - 1;
+        if (top_k >= 1 && (int64_t)top_k < V) {
+            jk = 0;
+            while (LV_END(jk) < (int64_t)top_k) ++jk;
+        }
+        int64_t jp = jk;
+        int cut_flag = 0;
+        if (top_p < 1.0) {
+            double T = top_p * lv_M[jk];
+            jp = 0;
+            while (jp < jk && !(lv_M[jp] >= T)) ++jp;
+            double below = jp > 0 ? lv_M[jp - 1] : 0.0;
+            if (T - below <= 1e-9 * T || lv_M[jp] - T <= 1e-9 * T) cut_flag = 1;
+        }
+        /* level race */
+        double s1 = -INFINITY, s2 = -INFINITY;
+        int64_t best = 0;
+        for (int64_t j = 0; j <= jp; ++j) {
+            double z = load_logit(row, dtype, (size_t)it[lv_first[j]].col);
+            double mass = (double)(LV_END(j) - lv_first[j]) * exp((z - z1) / tau);   /* n_j w_j */
+            double E = -log(e3o_uniform(e3o_noise_word(seed, grow, 3u, it[lv_first[j]].bits)));
+            double q = mass / E;
+            if (q > s1) { s2 = s1; s1 = q; best = j; }
+            else if (q > s2) s2 = q;
+        }
+        int tie_flag = (s2 > 0.0) && (s1 - s2 <= 1e-5 * s1);
+        /* column inside the level */
+        int64_t n = LV_END(best) - lv_first[best];
+        uint64_t k23 = (uint64_t)(e3o_noise_word(seed, grow, 4u, 0u) >> 9);
+        int64_t pos = (int64_t)(((2u * k23 + 1u) * (uint64_t)n) >> 24);
+        int32_t tok = it[lv_first[best] + pos].col;             /* items of a level are in column order */
+        token_out[r] = tok;
+        if (logp_out)
+            logp_out[r] = (load_logit(row, dtype, (size_t)tok) - z1) / tau - log(lv_M[jp]);
+        if (kept_out) kept_out[r] = (int32_t)LV_END(jp);
+        if (near_tie_out) near_tie_out[r] = (uint8_t)tie_flag;
+        if (near_cut_out) near_cut_out[r] = (uint8_t)cut_flag;
+        #undef LV_END
+        free(it); free(lv_first); free(lv_M);
+    }
+    return failed ? -1 : 0;
+}
+
 /*
  * Temperature update, Eq. 4: tau' = tau (1 + tau ln(alpha) / (ln|V| + ln ln|V|)),
  * alpha = H_target / H_t, H_target from e3o_entropy_target.  Readings: |V| is

@@ -75,6 +75,9 @@ def _declare(L):
     L.e3o_temperature_update_gap.restype = C.c_int
     L.e3o_grpo_objective.argtypes = [vp, vp, vp, vp, vp, i32, f64, vp, vp, vp]
     L.e3o_grpo_objective.restype = C.c_int
+    L.e3o_sample_restricted.argtypes = [vp, C.c_int, i64, i64, i64, vp, f32, i32, f64, u64, u64,
+                                        vp, vp, vp, vp, vp, C.c_int]
+    L.e3o_sample_restricted.restype = C.c_int
     L.e3o_max_threads.argtypes = []
     L.e3o_max_threads.restype = C.c_int
 
@@ -168,6 +171,36 @@ def sample_entropy(logits: np.ndarray, tau_rows: Optional[np.ndarray], tau_scala
     if rc != 0:
         raise RuntimeError(f"e3o_sample_entropy failed: {rc}")
     return SampleResult(tok, logp, ent, tie, diag)
+
+
+@dataclass
+class RestrictedResult:
+    token: np.ndarray      # int32 [rows]
+    logp: np.ndarray       # float64 [rows], under the truncated and renormalised distribution
+    kept: np.ndarray       # int32 [rows], columns that survive the truncation
+    near_tie: np.ndarray   # uint8 [rows]
+    near_cut: np.ndarray   # uint8 [rows]
+
+
+def sample_restricted(logits: np.ndarray, tau_rows: Optional[np.ndarray], tau_scalar: float,
+                      top_k: int, top_p: float, seed: int, row_base: int = 0,
+                      nthreads: int = 1) -> RestrictedResult:
+    """top_p crosses the library boundary as fp32 and is rounded the same way here."""
+    dt, rows, V, stride = _logits(logits)
+    if tau_rows is not None:
+        tau_rows = np.ascontiguousarray(tau_rows, dtype=np.float32)
+        assert tau_rows.shape == (rows,)
+    tok = np.empty(rows, dtype=np.int32)
+    logp = np.empty(rows, dtype=np.float64)
+    kept = np.empty(rows, dtype=np.int32)
+    tie = np.zeros(rows, dtype=np.uint8)
+    cut = np.zeros(rows, dtype=np.uint8)
+    rc = lib().e3o_sample_restricted(_ptr(logits), dt, rows, V, stride, _ptr(tau_rows), tau_scalar,
+                                     int(top_k), float(np.float32(top_p)), seed, row_base,
+                                     _ptr(tok), _ptr(logp), _ptr(kept), _ptr(tie), _ptr(cut), nthreads)
+    if rc != 0:
+        raise RuntimeError(f"e3o_sample_restricted failed: {rc}")
+    return RestrictedResult(tok, logp, kept, tie, cut)
 
 
 @dataclass
