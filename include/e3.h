@@ -111,6 +111,41 @@ int e3_sample_entropy(const void* logits, int dtype, int64_t rows, int64_t V, in
                       void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /*
+ * Rollout-side call with truncation: sample one token per row from the temperature-
+ * scaled softmax restricted to the top-k and / or top-p (nucleus) part of the row.
+ * The paper samples unrestricted (Section 5.1); this call covers the truncations that
+ * rollout engines offer.  bf16 logits only (E3_ERR_DTYPE for E3_F32).
+ *
+ * Definition (on value levels, so that it does not depend on the order of equal logits):
+ *   a level is the set of columns storing one bit pattern; levels are ranked by value,
+ *   highest first (-0 just below +0); level j has n_j columns and weight
+ *   w_j = exp((z_j - z_1) / tau);  C_j = n_1 + .. + n_j,  M_j = n_1 w_1 + .. + n_j w_j.
+ *   top_k >= 1: j_k = first j with C_j >= top_k (equal values at the cut are all kept);
+ *               0, or >= V: no count cut.
+ *   top_p < 1 : applied after top-k, to the distribution renormalised over levels
+ *               1..j_k: j_p = first j <= j_k with M_j >= top_p * M_{j_k};  >= 1: j_p = j_k.
+ *   The kept set is levels 1..j_p.  Draw: level = argmax_j n_j w_j / E_j with
+ *   E_j = -ln u_j, u_j = uniform of Philox stream 3 at index = the level's bit pattern
+ *   (same word -> uniform map as e3_sample_entropy; ties to the higher level); then
+ *   with k the 23-bit integer of stream 4, index 0: pos = ((2k+1) n_j) >> 24 and the
+ *   token is the pos-th column of the level in increasing column order.
+ * Outputs: token_out [rows] int32; logp_out [rows] fp32 = ln of the token's probability
+ *   under the truncated, renormalised distribution ((z_tok - z_1)/tau - ln M_{j_p});
+ *   kept_out [rows] int32 = C_{j_p}.  logp_out and kept_out may be NULL.
+ * Counts are exact; masses, the cuts and the race are evaluated in fp64.  A row whose
+ *   top_p target lies within 1e-9 (relative) of a cumulative mass may keep one level
+ *   more or less than an fp64 reference with another summation order.
+ * Logits must be finite (inf / NaN patterns are ignored as levels; a row without any
+ *   finite logit gives token 0, logp NaN, kept 0).  Other arguments, alignment rules and
+ *   errors as for e3_sample_entropy; top_k < 0 or top_p not in (0, inf): E3_ERR_VALUE.
+ * One workgroup of 1024 threads and 128 KiB of LDS per row.
+ */
+int e3_sample_restricted(const void* logits, int dtype, int64_t rows, int64_t V, int64_t row_stride,
+                         const float* tau_rows, float tau_scalar, int32_t top_k, float top_p,
+                         uint64_t seed, uint64_t row_base,
+                         int32_t* token_out, float* logp_out, int32_t* kept_out, void* hip_stream);
+
+/*
  * Training side: log-probability of a given token and the entropy of each row,
  * with the logits divided by the temperature as in the policy forward pass (end
  * of the "Temperature Scheduler" paragraph of Section 4.2), plus the two numbers

@@ -20,7 +20,8 @@ E3_F32, E3_BF16 = 0, 1
 E3_OK = 0
 E3_TILE_CHUNK, E3_TILE_LANES, E3_TILE_DEPTH = 8, 64, 16
 
-EXPORTS = ("e3_strerror", "e3_workspace_bytes", "e3_sample_entropy", "e3_logprob_entropy",
+EXPORTS = ("e3_strerror", "e3_workspace_bytes", "e3_sample_entropy", "e3_sample_restricted",
+           "e3_logprob_entropy",
            "e3_grpo_advantages", "e3_temperature_update", "e3_difficulty_ranks",
            "e3_allocate_budgets", "e3_budget_bounds", "e3_logprob_entropy_gap",
            "e3_temperature_update_gap", "e3_grpo_objective")
@@ -50,6 +51,9 @@ def lib() -> C.CDLL:
         L.e3_sample_entropy.argtypes = [vp, C.c_int, i64, i64, i64, vp, f32, u64, u64,
                                         vp, vp, vp, vp, C.c_size_t, vp]
         L.e3_sample_entropy.restype = C.c_int
+        L.e3_sample_restricted.argtypes = [vp, C.c_int, i64, i64, i64, vp, f32, i32, f32, u64, u64,
+                                           vp, vp, vp, vp]
+        L.e3_sample_restricted.restype = C.c_int
         L.e3_logprob_entropy.argtypes = [vp, C.c_int, i64, i64, i64, vp, vp, vp, f32,
                                          vp, vp, vp, vp, vp, C.c_size_t, vp]
         L.e3_logprob_entropy.restype = C.c_int
@@ -161,6 +165,33 @@ def e3_sample_entropy(logits: torch.Tensor, tau_rows: Optional[torch.Tensor], ta
     if rc != E3_OK:
         raise E3Error(rc, "e3_sample_entropy")
     return token_out, logp_out, entropy_out
+
+
+def e3_sample_restricted(logits: torch.Tensor, tau_rows: Optional[torch.Tensor], tau_scalar: float,
+                         top_k: int, top_p: float, seed: int, row_base: int = 0,
+                         token_out: Optional[torch.Tensor] = None,
+                         logp_out: Optional[torch.Tensor] = None,
+                         kept_out: Optional[torch.Tensor] = None):
+    """Returns (token int32 [rows], logp fp32 [rows], kept int32 [rows]); bf16 logits only."""
+    dt, rows, V, stride = _logits_meta(logits)
+    dev = logits.device
+    if token_out is None:
+        token_out = torch.empty(rows, dtype=torch.int32, device=dev)
+    if logp_out is None:
+        logp_out = torch.empty(rows, dtype=torch.float32, device=dev)
+    if kept_out is None:
+        kept_out = torch.empty(rows, dtype=torch.int32, device=dev)
+    _check(tau_rows, torch.float32, rows, "tau_rows", dev)
+    _check(token_out, torch.int32, rows, "token_out", dev)
+    _check(logp_out, torch.float32, rows, "logp_out", dev)
+    _check(kept_out, torch.int32, rows, "kept_out", dev)
+    rc = lib().e3_sample_restricted(_ptr(logits), dt, rows, V, stride, _ptr(tau_rows),
+                                    float(tau_scalar), int(top_k), float(top_p), int(seed),
+                                    int(row_base), _ptr(token_out), _ptr(logp_out), _ptr(kept_out),
+                                    _stream(dev))
+    if rc != E3_OK:
+        raise E3Error(rc, "e3_sample_restricted")
+    return token_out, logp_out, kept_out
 
 
 def e3_logprob_entropy(logits: torch.Tensor, target_ids: Optional[torch.Tensor],

@@ -74,6 +74,26 @@ extern "C" int e3_sample_entropy(const void* logits, int dtype, int64_t rows, in
     return err == hipSuccess ? E3_OK : E3_ERR_LAUNCH;
 }
 
+extern "C" int e3_sample_restricted(const void* logits, int dtype, int64_t rows, int64_t V,
+                                    int64_t row_stride, const float* tau_rows, float tau_scalar,
+                                    int32_t top_k, float top_p, uint64_t seed, uint64_t row_base,
+                                    int32_t* token_out, float* logp_out, int32_t* kept_out,
+                                    void* hip_stream)
+{
+    if (dtype == E3_F32) return E3_ERR_DTYPE;        // the level histogram needs 16-bit patterns
+    int rc = check_logits(logits, dtype, rows, V, row_stride);
+    if (rc != E3_OK) return rc;
+    rc = check_tau(tau_rows, tau_scalar);
+    if (rc != E3_OK) return rc;
+    if (top_k < 0 || !(top_p > 0.0f) || !std::isfinite(top_p)) return E3_ERR_VALUE;
+    if (rows == 0) return E3_OK;
+    if (token_out == nullptr) return E3_ERR_NULL;
+    hipError_t err = e3::launch_sample_restricted(logits, rows, V, row_stride, tau_rows, tau_scalar,
+                                                  top_k, top_p, seed, row_base, token_out, logp_out,
+                                                  kept_out, static_cast<hipStream_t>(hip_stream));
+    return err == hipSuccess ? E3_OK : E3_ERR_LAUNCH;
+}
+
 extern "C" int e3_logprob_entropy_gap(const void* logits, int dtype, int64_t rows, int64_t V,
                                       int64_t row_stride, const int32_t* target_ids,
                                       const uint8_t* row_mask, const float* tau_rows, float tau_scalar,

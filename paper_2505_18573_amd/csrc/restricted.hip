@@ -1,0 +1,520 @@
+// Restricted (top-k / top-p) sampling of bf16 logit rows for gfx950.
+//
+// Paper: arXiv 2505.18573 samples its rollouts unrestricted at temperature tau
+// (Section 5.1); rollout engines usually offer both truncations, so the definition is
+// the library's own and is stated in include/e3.h: columns that store one bit pattern
+// form a LEVEL, levels are ranked by value, the cuts are taken on cumulative level
+// counts (top-k) and cumulative level masses (top-p), and the draw is a Gumbel-max
+// over the kept levels followed by a uniform choice among the winning level's columns.
+//
+// bf16 has only 65,536 bit patterns, so a row's whole value distribution fits a
+// count histogram: 32,768 patterns (one sign) x 32-bit counters = 128 KiB of the
+// compute unit's 160 KiB LDS.  One workgroup of 16 waves owns one row:
+//   1. stream the row once, counting the non-negative patterns with LDS atomics
+//      (the columns of a wave instruction scatter over many bins: few conflicts);
+//   2. every thread owns 32 consecutive bins, i.e. 32 equally spaced values of one
+//      binade, whose weights exp((z - z_1)/tau) form a geometric sequence: two
+//      exponentials and 31 products per thread give all level masses in fp64; a
+//      workgroup scan yields the cumulative counts C_j and masses M_j in rank order;
+//   3. the cuts are located by the thread whose bins contain them, the kept levels
+//      race for the draw (n_j w_j / E_j, fp64), and a second sweep over the row (now
+//      in L2 / the memory-side cache) finds the pos-th column of the winning level.
+// Rows whose kept set reaches the negative patterns repeat steps 1-2 on the negative
+// half (same LDS); the rare order of events "top-k cut among the negatives, top-p cut
+// back among the non-negatives" costs a third sweep.  Everything a decision depends on
+// (counts, masses, race scores) is integer or fp64.
+#include "vocab_common.h"
+#include "vocab_pass.h"
+
+namespace e3 {
+namespace {
+
+constexpr int kRThreads = 1024;
+constexpr int kRWaves = kRThreads / 64;
+constexpr int kBins = 32768;            // bit patterns of one sign
+constexpr int kOwn = kBins / kRThreads; // 32 consecutive bins per thread
+
+struct RaceBest {
+    double q;        // n_j w_j / E_j, -1 = none
+    int bits;        // the level's stored bit pattern
+    int n;           // its column count
+};
+
+struct Shared {
+    double wave_M[kRWaves];
+    int wave_C[kRWaves];
+    float wave_top[kRWaves];
+    double best_q[kRWaves];
+    int best_bits[kRWaves];
+    int best_n[kRWaves];
+    int wave_hits[kRWaves];
+    int first_thread;
+    int cut_bin, cut_C;
+    double cut_M;
+    int token;
+};
+
+__device__ __forceinline__ double bf16_value(int bits)
+{
+    return (double)__uint_as_float((uint32_t)bits << 16);
+}
+
+// Bin <-> bit pattern.  Non-negative window: bin = pattern.  Negative window:
+// bin = 0xFFFF - pattern, so that in both windows a higher bin is a higher value.
+__device__ __forceinline__ int bin_bits(bool hi, int bin) { return hi ? bin : 0xFFFF - bin; }
+
+// Step 1: histogram of one sign's patterns over the whole row.
+__device__ __forceinline__ void build_hist(const uint16_t* __restrict__ row, int64_t V, bool hi, uint32_t* hist, int tid)
+{
+    const uint4 zero4 = {0u, 0u, 0u, 0u};
+    for (int i = tid; i < kBins / 4; i += kRThreads) reinterpret_cast<uint4*>(hist)[i] = zero4;
+    __syncthreads();
+    auto add = [&](uint32_t b16) {
+        const bool in_window = hi ? b16 < 0x8000u : b16 >= 0x8000u;
+        const uint32_t bin = hi ? b16 : 0xFFFFu - b16;
+        if (in_window) atomicAdd(&hist[bin], 1u);
+    };
+    auto add8 = [&](const u32x4& v) {
+        add(v.x & 0xFFFFu); add(v.x >> 16); add(v.y & 0xFFFFu); add(v.y >> 16);
+        add(v.z & 0xFFFFu); add(v.z >> 16); add(v.w & 0xFFFFu); add(v.w >> 16);
+    };
+    const int64_t nvec = V >> 3;
+    const u32x4* rv = reinterpret_cast<const u32x4*>(row);
+    int64_t v = tid;
+    for (; v + 3 * kRThreads < nvec; v += 4 * kRThreads) {
+        const u32x4 a = rv[v], b = rv[v + kRThreads], c = rv[v + 2 * kRThreads], d = rv[v + 3 * kRThreads];
+        add8(a); add8(b); add8(c); add8(d);
+    }
+    for (; v < nvec; v += kRThreads) add8(rv[v]);
+    const int64_t tail0 = nvec << 3;
+    if (tid < V - tail0) add((uint32_t)row[tail0 + tid]);
+    __syncthreads();
+}
+
+// Per-thread view of the scanned window.
+struct View {
+    uint32_t cnt[kOwn];   // counts of my bins; index kOwn-1 is my highest bin
+    int b0;               // my lowest bin
+    double w_top, r_inv;  // weight of my highest bin; factor to the next lower bin
+    int Cl, Cx;           // my count; count of all higher levels (carry included)
+    double Ml, Mx;        // the same for mass
+};
+
+// Step 2.  carry_C / carry_M: count and mass of all levels above this window.
+// z1: value of the row's highest level; when `find_z1` it is taken from this window's
+// highest populated bin (returns false if the window is empty).
+__device__ __forceinline__ bool scan_window(const uint32_t* hist, bool hi, double inv_tau, bool find_z1, double& z1,
+                            int carry_C, double carry_M, View& vw, int& Cw, double& Mw,
+                            Shared& sh, int tid)
+{
+    const int lane = tid & 63, wave = tid >> 6;
+    vw.b0 = kBins - kOwn * (tid + 1);                 // thread 0 owns the highest bins
+#pragma unroll
+    for (int i = 0; i < kOwn / 4; ++i) {
+        const uint4 c = reinterpret_cast<const uint4*>(hist + vw.b0)[i];
+        vw.cnt[4 * i] = c.x; vw.cnt[4 * i + 1] = c.y; vw.cnt[4 * i + 2] = c.z; vw.cnt[4 * i + 3] = c.w;
+    }
+    const int top_bits_field = (bin_bits(hi, vw.b0 + kOwn - 1) >> 7) & 0xFF;
+    const bool finite = top_bits_field != 0xFF;       // inf / NaN patterns are not levels
+    int Cl = 0, my_top = -1;
+#pragma unroll
+    for (int j = 0; j < kOwn; ++j) {
+        if (!finite) vw.cnt[j] = 0;
+        Cl += (int)vw.cnt[j];
+        if (vw.cnt[j] != 0) my_top = vw.b0 + j;
+    }
+    vw.Cl = Cl;
+    if (find_z1) {
+        const float t = wave_max((float)my_top);      // bins are below 2^15: exact in fp32
+        if (lane == 0) sh.wave_top[wave] = t;
+        __syncthreads();
+        float top = -1.0f;
+        for (int w = 0; w < kRWaves; ++w) top = fmaxf(top, sh.wave_top[w]);
+        __syncthreads();
+        if (top < 0.0f) { Cw = 0; Mw = 0.0; return false; }
+        z1 = bf16_value(bin_bits(hi, (int)top));
+    }
+    // my 32 values are equally spaced (one binade, or the subnormals): geometric weights
+    double Ml = 0.0;
+    vw.w_top = 0.0; vw.r_inv = 0.0;
+    if (Cl > 0) {
+        const double z_top = bf16_value(bin_bits(hi, vw.b0 + kOwn - 1));
+        const double step = ldexp(1.0, (top_bits_field ? top_bits_field : 1) - 134);
+        vw.w_top = exp((z_top - z1) * inv_tau);
+        vw.r_inv = exp(-step * inv_tau);
+        double w = vw.w_top;
+#pragma unroll
+        for (int j = kOwn - 1; j >= 0; --j) {
+            Ml += (double)vw.cnt[j] * w;
+            w *= vw.r_inv;
+        }
+    }
+    vw.Ml = Ml;
+    // exclusive scan in thread order (= rank order)
+    int Ci = Cl;
+    double Mi = Ml;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        const int c = __shfl_up(Ci, d, 64);
+        const double m = __shfl_up(Mi, d, 64);
+        if (lane >= d) { Ci += c; Mi += m; }
+    }
+    if (lane == 63) { sh.wave_C[wave] = Ci; sh.wave_M[wave] = Mi; }
+    __syncthreads();
+    int Cb = carry_C;
+    double Mb = carry_M;
+    int Ct = 0;
+    double Mt = 0.0;
+    for (int w = 0; w < kRWaves; ++w) {
+        if (w < wave) { Cb += sh.wave_C[w]; Mb += sh.wave_M[w]; }
+        Ct += sh.wave_C[w]; Mt += sh.wave_M[w];
+    }
+    __syncthreads();
+    vw.Cx = Cb + Ci - Cl;
+    vw.Mx = Mb + (Mi - Ml);
+    Cw = Ct; Mw = Mt;
+    return true;
+}
+
+// First level whose cumulative count reaches k.  Exactly one thread holds it.
+__device__ __forceinline__ void find_count_cut(const View& vw, int k, Shared& sh)
+{
+    if (vw.Cx < k && vw.Cx + vw.Cl >= k) {
+        int C = vw.Cx;
+        double M = vw.Mx, w = vw.w_top;
+        int bin = vw.b0;
+        bool done = false;
+#pragma unroll
+        for (int j = kOwn - 1; j >= 0; --j) {
+            if (!done) {
+                C += (int)vw.cnt[j];
+                M += (double)vw.cnt[j] * w;
+                if (C >= k) { bin = vw.b0 + j; done = true; }
+            }
+            w *= vw.r_inv;
+        }
+        sh.cut_bin = bin; sh.cut_C = C; sh.cut_M = M;
+    }
+    __syncthreads();
+}
+
+// First level at or above `floor_bin` whose cumulative mass reaches T.  The scan's
+// per-thread prefixes may disagree in the last bit, so the owner is the first thread
+// whose inclusive prefix reaches T; if rounding lets none of its levels reach T the
+// owner's lowest populated level (or the floor) is taken.
+__device__ __forceinline__ void find_mass_cut(const View& vw, double T, int floor_bin, int floor_C, double floor_M,
+                              Shared& sh, int tid)
+{
+    if (tid == 0) { sh.first_thread = kRThreads; }
+    __syncthreads();
+    if (vw.Cl > 0 && vw.Mx + vw.Ml >= T) atomicMin(&sh.first_thread, tid);
+    __syncthreads();
+    const int owner = sh.first_thread;
+    if (owner == kRThreads) {                        // nobody reaches T: keep down to the floor
+        if (tid == 0) { sh.cut_bin = floor_bin; sh.cut_C = floor_C; sh.cut_M = floor_M; }
+    } else if (tid == owner) {
+        int C = vw.Cx, bin = -1, Cb = 0;
+        double M = vw.Mx, w = vw.w_top, Mb = 0.0;
+        bool done = false;
+#pragma unroll
+        for (int j = kOwn - 1; j >= 0; --j) {
+            if (!done && vw.cnt[j] != 0) {
+                C += (int)vw.cnt[j];
+                M += (double)vw.cnt[j] * w;
+                bin = vw.b0 + j; Cb = C; Mb = M;      // lowest populated level so far
+                if (M >= T) done = true;
+            }
+            w *= vw.r_inv;
+        }
+        if (bin < floor_bin) { bin = floor_bin; Cb = floor_C; Mb = floor_M; }
+        sh.cut_bin = bin; sh.cut_C = Cb; sh.cut_M = Mb;
+    }
+    __syncthreads();
+}
+
+// Race of the levels in bins [cut_bin, kBins) of the window in LDS: maximise
+// n_j w_j / E_j with E_j = -ln u_j, u_j from Philox stream 3 at index = bit pattern.
+// Bins are dealt round-robin so that a short run of kept levels spreads over threads.
+__device__ __forceinline__ RaceBest race_window(const uint32_t* hist, bool hi, int cut_bin, double z1, double inv_tau,
+                                uint64_t seed, uint64_t grow, RaceBest best, Shared& sh, int tid)
+{
+    const int lane = tid & 63, wave = tid >> 6;
+    RaceBest mine{-1.0, 0, 0};
+    for (int bin = kBins - 1 - tid; bin >= cut_bin; bin -= kRThreads) {
+        const uint32_t n = hist[bin];
+        const int bits = bin_bits(hi, bin);
+        if (n == 0 || ((bits >> 7) & 0xFF) == 0xFF) continue;
+        uint32_t w4[4];
+        philox4x32_10((uint32_t)bits >> 2, (uint32_t)grow, (uint32_t)(grow >> 32), 3u,
+                      (uint32_t)seed, (uint32_t)(seed >> 32), w4);
+        const int sel = bits & 3;
+        const uint32_t word = sel == 0 ? w4[0] : sel == 1 ? w4[1] : sel == 2 ? w4[2] : w4[3];
+        const double u = ((double)(word >> 9) + 0.5) * (1.0 / 8388608.0);
+        const double q = (double)n * exp((bf16_value(bits) - z1) * inv_tau) / -log(u);
+        // a thread meets its bins in falling value order: `>` keeps the higher level on ties
+        if (q > mine.q) { mine.q = q; mine.bits = bits; mine.n = (int)n; }
+    }
+    // workgroup argmax; ties to the higher value = higher bin of this window
+    auto bin_of = [&](int bits) { return hi ? bits : 0xFFFF - bits; };
+#pragma unroll
+    for (int d = 32; d > 0; d >>= 1) {
+        const double oq = __shfl_xor(mine.q, d, 64);
+        const int ob = __shfl_xor(mine.bits, d, 64);
+        const int on = __shfl_xor(mine.n, d, 64);
+        if (oq > mine.q || (oq == mine.q && oq >= 0.0 && bin_of(ob) > bin_of(mine.bits))) {
+            mine.q = oq; mine.bits = ob; mine.n = on;
+        }
+    }
+    if (lane == 0) { sh.best_q[wave] = mine.q; sh.best_bits[wave] = mine.bits; sh.best_n[wave] = mine.n; }
+    __syncthreads();
+    RaceBest out = best;                              // an earlier (higher) window wins ties
+    bool from_here = false;
+    for (int w = 0; w < kRWaves; ++w) {
+        const double q = sh.best_q[w];
+        if (q > out.q || (from_here && q == out.q && q >= 0.0 && bin_of(sh.best_bits[w]) > bin_of(out.bits))) {
+            out.q = q; out.bits = sh.best_bits[w]; out.n = sh.best_n[w];
+            from_here = true;
+        }
+    }
+    __syncthreads();
+    return out;
+}
+
+// Step 3, last part: the pos-th column (0-based, increasing column order) that stores
+// `bits`.  Waves take contiguous runs of 16-byte vectors; the few columns past the last
+// whole vector come last.
+__device__ __forceinline__ int locate_column(const uint16_t* __restrict__ row, int64_t V, int bits, int pos,
+                             Shared& sh, int tid)
+{
+    const int lane = tid & 63, wave = tid >> 6;
+    const int64_t nvec = V >> 3;
+    const int64_t per_wave = (nvec + kRWaves - 1) / kRWaves;
+    const int64_t v_begin = (int64_t)wave * per_wave < nvec ? (int64_t)wave * per_wave : nvec;
+    const int64_t v_end = v_begin + per_wave < nvec ? v_begin + per_wave : nvec;
+    const u32x4* rv = reinterpret_cast<const u32x4*>(row);
+    const uint32_t pat = (uint32_t)bits;
+    auto mask_of = [&](const u32x4& v) -> uint32_t {
+        uint32_t m = 0;
+        m |= ((v.x & 0xFFFFu) == pat) << 0; m |= ((v.x >> 16) == pat) << 1;
+        m |= ((v.y & 0xFFFFu) == pat) << 2; m |= ((v.y >> 16) == pat) << 3;
+        m |= ((v.z & 0xFFFFu) == pat) << 4; m |= ((v.z >> 16) == pat) << 5;
+        m |= ((v.w & 0xFFFFu) == pat) << 6; m |= ((v.w >> 16) == pat) << 7;
+        return m;
+    };
+    // hits of my wave's run
+    int hits = 0;
+    for (int64_t v = v_begin + lane; v < v_end; v += 64) hits += __popc(mask_of(rv[v]));
+#pragma unroll
+    for (int d = 32; d > 0; d >>= 1) hits += __shfl_xor(hits, d, 64);
+    if (lane == 0) sh.wave_hits[wave] = hits;
+    if (tid == 0) sh.token = -1;
+    __syncthreads();
+    int before = 0;
+    for (int w = 0; w < wave; ++w) before += sh.wave_hits[w];
+    int total = 0;
+    for (int w = 0; w < kRWaves; ++w) total += sh.wave_hits[w];
+    if (pos >= before && pos < before + hits) {       // uniform per wave: my run holds it
+        int rem = pos - before;
+        for (int64_t v0 = v_begin; v0 < v_end; v0 += 64) {
+            const int64_t v = v0 + lane;
+            const uint32_t m = v < v_end ? mask_of(rv[v]) : 0u;
+            const int c = __popc(m);
+            int inc = c;
+#pragma unroll
+            for (int d = 1; d < 64; d <<= 1) {
+                const int o = __shfl_up(inc, d, 64);
+                if (lane >= d) inc += o;
+            }
+            const int sweep_total = __shfl(inc, 63, 64);
+            if (rem < sweep_total) {
+                if (rem >= inc - c && rem < inc) {    // exactly one lane
+                    int skip = rem - (inc - c);
+                    uint32_t mm = m;
+                    while (skip-- > 0) mm &= mm - 1;  // drop the lowest set bits
+                    sh.token = (int)(v * 8 + (__ffs(mm) - 1));
+                }
+                break;
+            }
+            rem -= sweep_total;
+        }
+    }
+    // the columns after the last whole vector
+    if (tid == 0 && pos >= total) {
+        int rem = pos - total;
+        for (int64_t c = nvec << 3; c < V; ++c)
+            if ((uint32_t)row[c] == pat && rem-- == 0) { sh.token = (int)c; break; }
+    }
+    __syncthreads();
+    return sh.token;
+}
+
+struct RestrictedArgs {
+    const uint16_t* logits;
+    int64_t rows, V, row_stride;
+    const float* tau_rows;
+    float tau_scalar;
+    int32_t top_k;
+    float top_p;
+    uint64_t seed, row_base;
+    int32_t* token_out;
+    float* logp_out;
+    int32_t* kept_out;
+};
+
+__global__ __launch_bounds__(kRThreads)
+void sample_restricted_kernel(RestrictedArgs a)
+{
+    __shared__ __align__(16) uint32_t hist[kBins];
+    __shared__ Shared sh;
+    const int tid = threadIdx.x;
+    const int64_t row = blockIdx.x;
+    const int64_t V = a.V;
+    const uint16_t* rowp = a.logits + row * a.row_stride;
+    const float tau = a.tau_rows ? a.tau_rows[row] : a.tau_scalar;
+    const double inv_tau = 1.0 / (double)tau;
+    const uint64_t grow = a.row_base + (uint64_t)row;
+    const bool k_on = a.top_k >= 1 && (int64_t)a.top_k < V;
+    const bool p_on = a.top_p < 1.0f;
+    const double p = (double)a.top_p;
+    const int k = a.top_k;
+
+    View vw;
+    double z1 = 0.0;
+    int C_hi = 0, C_lo = 0;
+    double M_hi = 0.0, M_lo = 0.0;
+    RaceBest best{-1.0, 0, 0};
+    int kept_C = 0;
+    double kept_M = 0.0;
+
+    // Without top-k the nucleus target is a fraction of the whole row's mass, which
+    // includes the negative patterns: total them first, relative to the value 0.
+    double neg_mass_ref0 = 0.0;
+    if (!k_on && p_on) {
+        build_hist(rowp, V, false, hist, tid);
+        double zero_ref = 0.0;
+        int Cn;
+        scan_window(hist, false, inv_tau, false, zero_ref, 0, 0.0, vw, Cn, neg_mass_ref0, sh, tid);
+    }
+
+    build_hist(rowp, V, true, hist, tid);
+    const bool any_hi = scan_window(hist, true, inv_tau, true, z1, 0, 0.0, vw, C_hi, M_hi, sh, tid);
+
+    // Does the kept set end inside the non-negative window?
+    bool cut_in_hi = false;
+    if (any_hi) {
+        if (k_on) {
+            if (C_hi >= k) {
+                find_count_cut(vw, k, sh);
+                const int kb = sh.cut_bin, kC = sh.cut_C;
+                const double kM = sh.cut_M;
+                __syncthreads();
+                if (p_on) find_mass_cut(vw, p * kM, kb, kC, kM, sh, tid);
+                cut_in_hi = true;
+            }
+        } else if (p_on) {
+            const double T = p * (M_hi + neg_mass_ref0 * exp(-z1 * inv_tau));
+            if (M_hi >= T) {
+                find_mass_cut(vw, T, 0, C_hi, M_hi, sh, tid);
+                cut_in_hi = true;
+            }
+        }
+        if (cut_in_hi) {
+            const int cb = sh.cut_bin;
+            kept_C = sh.cut_C; kept_M = sh.cut_M;
+            __syncthreads();
+            best = race_window(hist, true, cb, z1, inv_tau, a.seed, grow, best, sh, tid);
+        } else {
+            best = race_window(hist, true, 0, z1, inv_tau, a.seed, grow, best, sh, tid);
+            kept_C = C_hi; kept_M = M_hi;
+        }
+    }
+
+    if (!cut_in_hi) {
+        // The kept set reaches the negative patterns (or the row has no others).
+        build_hist(rowp, V, false, hist, tid);
+        const bool any_lo = scan_window(hist, false, inv_tau, !any_hi, z1, C_hi, M_hi, vw, C_lo, M_lo, sh, tid);
+        if (any_lo) {
+            int cb = 0;
+            int cC = C_hi + C_lo;
+            double cM = M_hi + M_lo;
+            bool back_to_hi = false;
+            if (k_on) {
+                if (C_hi + C_lo >= k && C_hi < k) {
+                    find_count_cut(vw, k, sh);
+                    cb = sh.cut_bin; cC = sh.cut_C; cM = sh.cut_M;
+                    __syncthreads();
+                }
+                if (p_on) {
+                    const double T = p * cM;
+                    if (any_hi && M_hi >= T) back_to_hi = true;       // nucleus ends above this window
+                    else {
+                        find_mass_cut(vw, T, cb, cC, cM, sh, tid);
+                        cb = sh.cut_bin; cC = sh.cut_C; cM = sh.cut_M;
+                        __syncthreads();
+                    }
+                }
+            } else if (p_on) {
+                const double T = p * (M_hi + M_lo);
+                find_mass_cut(vw, T, 0, cC, cM, sh, tid);
+                cb = sh.cut_bin; cC = sh.cut_C; cM = sh.cut_M;
+                __syncthreads();
+            }
+            if (!back_to_hi) {
+                best = race_window(hist, false, cb, z1, inv_tau, a.seed, grow, best, sh, tid);
+                kept_C = cC; kept_M = cM;
+            } else {
+                // third sweep: the top-k cut lies among the negatives, the nucleus of that
+                // set ends among the non-negatives
+                const double T = p * cM;
+                int Cd; double Md;
+                build_hist(rowp, V, true, hist, tid);
+                scan_window(hist, true, inv_tau, false, z1, 0, 0.0, vw, Cd, Md, sh, tid);
+                find_mass_cut(vw, T, 0, C_hi, M_hi, sh, tid);
+                const int hb = sh.cut_bin;
+                kept_C = sh.cut_C; kept_M = sh.cut_M;
+                __syncthreads();
+                best = race_window(hist, true, hb, z1, inv_tau, a.seed, grow, RaceBest{-1.0, 0, 0}, sh, tid);
+            }
+        }
+    }
+
+    // the column inside the winning level
+    uint32_t w4[4];
+    philox4x32_10(0u, (uint32_t)grow, (uint32_t)(grow >> 32), 4u, (uint32_t)a.seed, (uint32_t)(a.seed >> 32), w4);
+    const uint64_t k23 = (uint64_t)(w4[0] >> 9);
+    int tok = 0;
+    if (best.q >= 0.0) {
+        const int pos = (int)(((2u * k23 + 1u) * (uint64_t)best.n) >> 24);
+        tok = locate_column(rowp, V, best.bits, pos, sh, tid);
+        if (tok < 0 || tok >= V) tok = 0;             // only reachable with non-finite input
+    }
+    if (tid == 0) {
+        a.token_out[row] = tok;
+        if (a.kept_out) a.kept_out[row] = kept_C;
+        if (a.logp_out)
+            a.logp_out[row] = best.q >= 0.0
+                ? (float)((bf16_value(best.bits) - z1) * inv_tau - log(kept_M))
+                : __builtin_nanf("");
+    }
+}
+
+}  // namespace
+
+hipError_t launch_sample_restricted(const void* logits, int64_t rows, int64_t V, int64_t row_stride,
+                                    const float* tau_rows, float tau_scalar, int32_t top_k, float top_p,
+                                    uint64_t seed, uint64_t row_base, int32_t* token_out,
+                                    float* logp_out, int32_t* kept_out, hipStream_t stream)
+{
+    if (rows == 0) return hipSuccess;
+    RestrictedArgs a;
+    a.logits = static_cast<const uint16_t*>(logits);
+    a.rows = rows; a.V = V; a.row_stride = row_stride;
+    a.tau_rows = tau_rows; a.tau_scalar = tau_scalar;
+    a.top_k = top_k; a.top_p = top_p;
+    a.seed = seed; a.row_base = row_base;
+    a.token_out = token_out; a.logp_out = logp_out; a.kept_out = kept_out;
+    hipLaunchKernelGGL(sample_restricted_kernel, dim3((unsigned)rows), dim3(kRThreads), 0, stream, a);
+    return hipGetLastError();
+}
+
+}  // namespace e3

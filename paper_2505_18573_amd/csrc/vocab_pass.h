@@ -32,6 +32,12 @@ bool vocab_pass_fits(int64_t V);
 hipError_t launch_entropy_reduce(const float* entropy, const uint8_t* mask, int64_t rows,
                                  double* sum_out, int64_t* count_out, hipStream_t stream);
 
+// top-k / top-p restricted sampling of bf16 rows (one workgroup per row)
+hipError_t launch_sample_restricted(const void* logits, int64_t rows, int64_t V, int64_t row_stride,
+                                    const float* tau_rows, float tau_scalar, int32_t top_k, float top_p,
+                                    uint64_t seed, uint64_t row_base, int32_t* token_out,
+                                    float* logp_out, int32_t* kept_out, hipStream_t stream);
+
 hipError_t launch_grpo_advantages(const float* rewards, const int32_t* offsets, int32_t num_groups,
                                   int32_t ddof, float eps, float* adv_out, hipStream_t stream);
 
