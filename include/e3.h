@@ -132,9 +132,10 @@ int e3_sample_entropy(const void* logits, int dtype, int64_t rows, int64_t V, in
  * Outputs: token_out [rows] int32; logp_out [rows] fp32 = ln of the token's probability
  *   under the truncated, renormalised distribution ((z_tok - z_1)/tau - ln M_{j_p});
  *   kept_out [rows] int32 = C_{j_p}.  logp_out and kept_out may be NULL.
- * Counts are exact; masses, the cuts and the race are evaluated in fp64.  A row whose
- *   top_p target lies within 1e-9 (relative) of a cumulative mass may keep one level
- *   more or less than an fp64 reference with another summation order.
+ * Counts are exact; masses and the cuts are evaluated in fp64, the race scores in fp32.
+ *   A row whose top_p target lies within 1e-9 (relative) of a cumulative mass may keep one
+ *   level more or less than an fp64 reference with another summation order, and a row
+ *   whose two best race scores lie within 1e-5 (relative) may draw the other level.
  * Logits must be finite (inf / NaN patterns are ignored as levels; a row without any
  *   finite logit gives token 0, logp NaN, kept 0).  Other arguments, alignment rules and
  *   errors as for e3_sample_entropy; top_k < 0 or top_p not in (0, inf): E3_ERR_VALUE.

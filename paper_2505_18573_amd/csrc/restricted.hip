@@ -17,12 +17,13 @@
 //      exponentials and 31 products per thread give all level masses in fp64; a
 //      workgroup scan yields the cumulative counts C_j and masses M_j in rank order;
 //   3. the cuts are located by the thread whose bins contain them, the kept levels
-//      race for the draw (n_j w_j / E_j, fp64), and a second sweep over the row (now
-//      in L2 / the memory-side cache) finds the pos-th column of the winning level.
+//      race for the draw (n_j w_j / E_j, fp32 like the unrestricted sampler), and a
+//      second sweep over the row (now in L2 / the memory-side cache) finds the pos-th
+//      column of the winning level.
 // Rows whose kept set reaches the negative patterns repeat steps 1-2 on the negative
 // half (same LDS); the rare order of events "top-k cut among the negatives, top-p cut
-// back among the non-negatives" costs a third sweep.  Everything a decision depends on
-// (counts, masses, race scores) is integer or fp64.
+// back among the non-negatives" costs a third sweep.  Counts are integers; masses and
+// the cuts are fp64.
 #include "vocab_common.h"
 #include "vocab_pass.h"
 
@@ -52,7 +53,10 @@ struct Shared {
     int cut_bin, cut_C;
     double cut_M;
     int token;
+    int list_n;
+    uint32_t list[1024];   // (vector index << 8 | 8-bit column mask) of vectors holding the winner
 };
+constexpr int kListCap = 1024;
 
 __device__ __forceinline__ double bf16_value(int bits)
 {
@@ -234,11 +238,15 @@ __device__ __forceinline__ void find_mass_cut(const View& vw, double T, int floo
 
 // Race of the levels in bins [cut_bin, kBins) of the window in LDS: maximise
 // n_j w_j / E_j with E_j = -ln u_j, u_j from Philox stream 3 at index = bit pattern.
+// The scores are formed in fp32 (weights and variates as in the unrestricted sampler);
+// decisions closer than fp32 resolves are the near-ties the parity rule exempts.
 // Bins are dealt round-robin so that a short run of kept levels spreads over threads.
-__device__ __forceinline__ RaceBest race_window(const uint32_t* hist, bool hi, int cut_bin, double z1, double inv_tau,
-                                uint64_t seed, uint64_t grow, RaceBest best, Shared& sh, int tid)
+__device__ __forceinline__ RaceBest race_window(const uint32_t* hist, bool hi, int cut_bin, double z1,
+                                                float c, uint64_t seed, uint64_t grow, RaceBest best,
+                                                Shared& sh, int tid)
 {
     const int lane = tid & 63, wave = tid >> 6;
+    const float z1f = (float)z1;                      // a bf16 value: exact
     RaceBest mine{-1.0, 0, 0};
     for (int bin = kBins - 1 - tid; bin >= cut_bin; bin -= kRThreads) {
         const uint32_t n = hist[bin];
@@ -249,10 +257,10 @@ __device__ __forceinline__ RaceBest race_window(const uint32_t* hist, bool hi, i
                       (uint32_t)seed, (uint32_t)(seed >> 32), w4);
         const int sel = bits & 3;
         const uint32_t word = sel == 0 ? w4[0] : sel == 1 ? w4[1] : sel == 2 ? w4[2] : w4[3];
-        const double u = ((double)(word >> 9) + 0.5) * (1.0 / 8388608.0);
-        const double q = (double)n * exp((bf16_value(bits) - z1) * inv_tau) / -log(u);
+        const float z = __uint_as_float((uint32_t)bits << 16);
+        const float q = (float)n * __builtin_amdgcn_exp2f((z - z1f) * c) / exp_variate(word);
         // a thread meets its bins in falling value order: `>` keeps the higher level on ties
-        if (q > mine.q) { mine.q = q; mine.bits = bits; mine.n = (int)n; }
+        if ((double)q > mine.q) { mine.q = (double)q; mine.bits = bits; mine.n = (int)n; }
     }
     // workgroup argmax; ties to the higher value = higher bin of this window
     auto bin_of = [&](int bits) { return hi ? bits : 0xFFFF - bits; };
@@ -280,8 +288,75 @@ __device__ __forceinline__ RaceBest race_window(const uint32_t* hist, bool hi, i
     return out;
 }
 
-// Step 3, last part: the pos-th column (0-based, increasing column order) that stores
-// `bits`.  Waves take contiguous runs of 16-byte vectors; the few columns past the last
+// Step 3, last part, when the winning level has at most kListCap columns (the usual
+// case): one pipelined sweep over the row in which every thread notes the vectors that
+// hold the pattern in a short LDS list; the pos-th column in column order is then picked
+// from the list by ranking its entries.
+__device__ __forceinline__ int locate_listed(const uint16_t* __restrict__ row, int64_t V, int bits,
+                                             int pos, Shared& sh, int tid)
+{
+    if (tid == 0) { sh.list_n = 0; sh.token = -1; }
+    __syncthreads();
+    const int64_t nvec = V >> 3;
+    const u32x4* rv = reinterpret_cast<const u32x4*>(row);
+    const uint32_t pat = (uint32_t)bits, pat2 = pat | (pat << 16);
+    auto zero_half = [](uint32_t x) -> uint32_t { return (x - 0x00010001u) & ~x & 0x80008000u; };
+    auto note = [&](int64_t v, const u32x4& t) {
+        const uint32_t a = t.x ^ pat2, b = t.y ^ pat2, c = t.z ^ pat2, d = t.w ^ pat2;
+        if ((zero_half(a) | zero_half(b) | zero_half(c) | zero_half(d)) != 0u) {
+            uint32_t m = 0;
+            m |= ((a & 0xFFFFu) == 0u) << 0; m |= ((a >> 16) == 0u) << 1;
+            m |= ((b & 0xFFFFu) == 0u) << 2; m |= ((b >> 16) == 0u) << 3;
+            m |= ((c & 0xFFFFu) == 0u) << 4; m |= ((c >> 16) == 0u) << 5;
+            m |= ((d & 0xFFFFu) == 0u) << 6; m |= ((d >> 16) == 0u) << 7;
+            if (m != 0u) {
+                const int slot = atomicAdd(&sh.list_n, 1);
+                if (slot < kListCap) sh.list[slot] = ((uint32_t)v << 8) | m;
+            }
+        }
+    };
+    const u32x4 filler = {~pat2, ~pat2, ~pat2, ~pat2};           // matches nothing
+    for (int64_t v0 = tid; v0 < nvec; v0 += 8 * kRThreads) {
+        u32x4 t[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const int64_t vv = v0 + (int64_t)j * kRThreads;
+            t[j] = vv < nvec ? rv[vv] : filler;
+        }
+#pragma unroll
+        for (int j = 0; j < 8; ++j) note(v0 + (int64_t)j * kRThreads, t[j]);
+    }
+    if (tid == 0) {                                              // columns after the last whole vector
+        uint32_t m = 0;
+        for (int64_t c = nvec << 3; c < V; ++c)
+            if ((uint32_t)row[c] == pat) m |= 1u << (int)(c - (nvec << 3));
+        if (m != 0u) {
+            const int slot = atomicAdd(&sh.list_n, 1);
+            if (slot < kListCap) sh.list[slot] = ((uint32_t)nvec << 8) | m;
+        }
+    }
+    __syncthreads();
+    const int cnt = sh.list_n < kListCap ? sh.list_n : kListCap;
+    if (tid < cnt) {
+        const uint32_t mine = sh.list[tid];
+        int rank = 0;
+        for (int e = 0; e < cnt; ++e) {
+            const uint32_t o = sh.list[e];
+            if ((o >> 8) < (mine >> 8)) rank += __popc(o & 0xFFu);
+        }
+        const int here = __popc(mine & 0xFFu);
+        if (pos >= rank && pos < rank + here) {
+            uint32_t mm = mine & 0xFFu;
+            for (int skip = pos - rank; skip > 0; --skip) mm &= mm - 1;   // drop the lowest set bits
+            sh.token = (int)((mine >> 8) * 8u) + (__ffs(mm) - 1);
+        }
+    }
+    __syncthreads();
+    return sh.token;
+}
+
+// Step 3, last part, for levels of any size: the pos-th column (0-based, increasing
+// column order) that stores `bits`, by counting.  Waves take contiguous runs of 16-byte vectors; the few columns past the last
 // whole vector come last.
 __device__ __forceinline__ int locate_column(const uint16_t* __restrict__ row, int64_t V, int bits, int pos,
                              Shared& sh, int tid)
@@ -372,6 +447,7 @@ void sample_restricted_kernel(RestrictedArgs a)
     const uint16_t* rowp = a.logits + row * a.row_stride;
     const float tau = a.tau_rows ? a.tau_rows[row] : a.tau_scalar;
     const double inv_tau = 1.0 / (double)tau;
+    const float c = kLog2eF / tau;
     const uint64_t grow = a.row_base + (uint64_t)row;
     const bool k_on = a.top_k >= 1 && (int64_t)a.top_k < V;
     const bool p_on = a.top_p < 1.0f;
@@ -422,9 +498,9 @@ void sample_restricted_kernel(RestrictedArgs a)
             const int cb = sh.cut_bin;
             kept_C = sh.cut_C; kept_M = sh.cut_M;
             __syncthreads();
-            best = race_window(hist, true, cb, z1, inv_tau, a.seed, grow, best, sh, tid);
+            best = race_window(hist, true, cb, z1, c, a.seed, grow, best, sh, tid);
         } else {
-            best = race_window(hist, true, 0, z1, inv_tau, a.seed, grow, best, sh, tid);
+            best = race_window(hist, true, 0, z1, c, a.seed, grow, best, sh, tid);
             kept_C = C_hi; kept_M = M_hi;
         }
     }
@@ -460,7 +536,7 @@ void sample_restricted_kernel(RestrictedArgs a)
                 __syncthreads();
             }
             if (!back_to_hi) {
-                best = race_window(hist, false, cb, z1, inv_tau, a.seed, grow, best, sh, tid);
+                best = race_window(hist, false, cb, z1, c, a.seed, grow, best, sh, tid);
                 kept_C = cC; kept_M = cM;
             } else {
                 // third sweep: the top-k cut lies among the negatives, the nucleus of that
@@ -473,7 +549,7 @@ void sample_restricted_kernel(RestrictedArgs a)
                 const int hb = sh.cut_bin;
                 kept_C = sh.cut_C; kept_M = sh.cut_M;
                 __syncthreads();
-                best = race_window(hist, true, hb, z1, inv_tau, a.seed, grow, RaceBest{-1.0, 0, 0}, sh, tid);
+                best = race_window(hist, true, hb, z1, c, a.seed, grow, RaceBest{-1.0, 0, 0}, sh, tid);
             }
         }
     }
@@ -485,7 +561,8 @@ void sample_restricted_kernel(RestrictedArgs a)
     int tok = 0;
     if (best.q >= 0.0) {
         const int pos = (int)(((2u * k23 + 1u) * (uint64_t)best.n) >> 24);
-        tok = locate_column(rowp, V, best.bits, pos, sh, tid);
+        tok = best.n <= kListCap ? locate_listed(rowp, V, best.bits, pos, sh, tid)
+                                 : locate_column(rowp, V, best.bits, pos, sh, tid);
         if (tok < 0 || tok >= V) tok = 0;             // only reachable with non-finite input
     }
     if (tid == 0) {
