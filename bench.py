@@ -50,6 +50,9 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--buffers", type=int, default=8, help="distinct logit buffers rotated over")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--restricted", action="store_true",
+                    help="also time e3_sample_restricted (top-k 50, top-p 0.95) on the same batches and "
+                         "report it in a `restricted_sampling` object; not part of the step")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run a plain device copy of one logit buffer 10 times (a kernel of "
                          "known traffic: 155.6 MB read + 155.6 MB written) so that a rocprofv3 "
@@ -192,10 +195,40 @@ def main() -> int:
         "scheduler": {"tau_after": state["tau"], "H_init": state["H_init"]},
     }
 
+    if args.restricted:
+        out["restricted_sampling"] = restricted_leg(e3, batches, stream)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(batches[0], rewards, offsets)
     print(json.dumps(out))
     return 0
+
+
+def restricted_leg(e3, batches, stream, reps: int = 50):
+    """Top-k / top-p sampling of the same decode batches (HIP events around each launch)."""
+    dev = batches[0].logits.device
+    tok = torch.empty(ROWS, dtype=torch.int32, device=dev)
+    lp = torch.empty(ROWS, dtype=torch.float32, device=dev)
+    kept = torch.empty(ROWS, dtype=torch.int32, device=dev)
+    res = {}
+    for name, k, p in (("top_k50", 50, 1.0), ("top_k50_top_p0.95", 50, 0.95), ("top_p0.9", 0, 0.9)):
+        evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+               for _ in range(reps)]
+        for i in range(5 + reps):
+            b = batches[i % len(batches)]
+            if i >= 5:
+                evs[i - 5][0].record(stream)
+            e3.e3_sample_restricted(b.logits, b.tau_rows, 1.0, k, p, seed=7, row_base=i * ROWS,
+                                    token_out=tok, logp_out=lp, kept_out=kept)
+            if i >= 5:
+                evs[i - 5][1].record(stream)
+        torch.cuda.synchronize()
+        ms = sorted(a.elapsed_time(b) for a, b in evs)
+        avg = sum(ms) / len(ms)
+        res[name] = {"avg_ms": avg, "median_ms": ms[len(ms) // 2], "rows_per_s": ROWS / (avg * 1e-3),
+                     "logit_GBps": ROWS * V * 2 / (avg * 1e-3) / 1e9,
+                     "frac_of_hbm_peak": ROWS * V * 2 / (avg * 1e-3) / 1e9 / HBM_PEAK_GBPS,
+                     "mean_kept": float(kept.float().mean().item())}
+    return res
 
 
 def cpu_baseline(batch, rewards, offsets):
