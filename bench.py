@@ -195,12 +195,38 @@ def main() -> int:
         "scheduler": {"tau_after": state["tau"], "H_init": state["H_init"]},
     }
 
+    out["read_ceiling"] = read_ceiling_leg(e3, batches, stream, pair_ms)
+    out["roofline"]["frac_of_read_ceiling"] = achieved / out["read_ceiling"]["GBps"]
     if args.restricted:
         out["restricted_sampling"] = restricted_leg(e3, batches, stream)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(batches[0], rewards, offsets)
     print(json.dumps(out))
     return 0
+
+
+def read_ceiling_leg(e3, batches, stream, pair_ms, reps: int = 50):
+    """What a pure read of the same logit buffers reaches on this machine, timed exactly like
+    the sample kernel (one HIP event pair per launch on a busy stream, rotating buffers)."""
+    dev = batches[0].logits.device
+    sums = torch.empty(e3.binding.E3_READ_PROBE_SUMS, dtype=torch.int32, device=dev)
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+           for _ in range(reps)]
+    for i in range(5 + reps):
+        b = batches[i % len(batches)]
+        if i >= 5:
+            evs[i - 5][0].record(stream)
+        e3.e3_read_probe(b.logits, sums)
+        if i >= 5:
+            evs[i - 5][1].record(stream)
+    torch.cuda.synchronize()
+    ms = sorted(a.elapsed_time(b) for a, b in evs)
+    avg = sum(ms) / len(ms)
+    nbytes = ROWS * V * 2
+    return {"kernel": "read_probe_kernel (16-byte non-temporal loads, xor checksum only)",
+            "avg_ms": avg, "median_ms": ms[len(ms) // 2], "GBps": nbytes / (avg * 1e-3) / 1e9,
+            "frac_of_hbm_peak": nbytes / (avg * 1e-3) / 1e9 / HBM_PEAK_GBPS,
+            "avg_ms_minus_empty_pair": avg - pair_ms}
 
 
 def restricted_leg(e3, batches, stream, reps: int = 50):

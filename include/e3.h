@@ -111,6 +111,18 @@ int e3_sample_entropy(const void* logits, int dtype, int64_t rows, int64_t V, in
                       void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /*
+ * Diagnostic, for callers that measure: read `bytes` bytes of device memory once, with
+ * the access pattern of the vocabulary pass (16-byte non-temporal loads), and write
+ * E3_READ_PROBE_SUMS xor checksums (one per workgroup; their xor is the xor of all
+ * 32-bit words of the buffer) to sums_out [E3_READ_PROBE_SUMS] uint32, device.  It performs
+ * none of the method's arithmetic: timing it on the same buffers gives the read rate that
+ * the kernels' achieved GB/s can be compared with.  bytes must be a multiple of 16
+ * (E3_ERR_SHAPE) and buf 16-byte aligned (E3_ERR_ALIGN); bytes == 0 writes zeros.
+ */
+#define E3_READ_PROBE_SUMS 2048
+int e3_read_probe(const void* buf, int64_t bytes, uint32_t* sums_out, void* hip_stream);
+
+/*
  * Rollout-side call with truncation: sample one token per row from the temperature-
  * scaled softmax restricted to the top-k and / or top-p (nucleus) part of the row.
  * The paper samples unrestricted (Section 5.1); this call covers the truncations that

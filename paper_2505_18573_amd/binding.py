@@ -24,7 +24,7 @@ EXPORTS = ("e3_strerror", "e3_workspace_bytes", "e3_sample_entropy", "e3_sample_
            "e3_logprob_entropy",
            "e3_grpo_advantages", "e3_temperature_update", "e3_difficulty_ranks",
            "e3_allocate_budgets", "e3_budget_bounds", "e3_logprob_entropy_gap",
-           "e3_temperature_update_gap", "e3_grpo_objective")
+           "e3_temperature_update_gap", "e3_grpo_objective", "e3_read_probe")
 
 _lib: Optional[C.CDLL] = None
 
@@ -54,6 +54,8 @@ def lib() -> C.CDLL:
         L.e3_sample_restricted.argtypes = [vp, C.c_int, i64, i64, i64, vp, f32, i32, f32, u64, u64,
                                            vp, vp, vp, vp]
         L.e3_sample_restricted.restype = C.c_int
+        L.e3_read_probe.argtypes = [vp, i64, vp, vp]
+        L.e3_read_probe.restype = C.c_int
         L.e3_logprob_entropy.argtypes = [vp, C.c_int, i64, i64, i64, vp, vp, vp, f32,
                                          vp, vp, vp, vp, vp, C.c_size_t, vp]
         L.e3_logprob_entropy.restype = C.c_int
@@ -192,6 +194,23 @@ def e3_sample_restricted(logits: torch.Tensor, tau_rows: Optional[torch.Tensor],
     if rc != E3_OK:
         raise E3Error(rc, "e3_sample_restricted")
     return token_out, logp_out, kept_out
+
+
+E3_READ_PROBE_SUMS = 2048
+
+
+def e3_read_probe(buf: torch.Tensor, sums_out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """Reads the (contiguous) tensor once; returns the E3_READ_PROBE_SUMS xor checksums (int32)."""
+    if not buf.is_cuda or not buf.is_contiguous():
+        raise ValueError("buf must be a contiguous GPU tensor")
+    dev = buf.device
+    if sums_out is None:
+        sums_out = torch.empty(E3_READ_PROBE_SUMS, dtype=torch.int32, device=dev)
+    _check(sums_out, torch.int32, E3_READ_PROBE_SUMS, "sums_out", dev)
+    rc = lib().e3_read_probe(_ptr(buf), buf.numel() * buf.element_size(), _ptr(sums_out), _stream(dev))
+    if rc != E3_OK:
+        raise E3Error(rc, "e3_read_probe")
+    return sums_out
 
 
 def e3_logprob_entropy(logits: torch.Tensor, target_ids: Optional[torch.Tensor],

@@ -74,6 +74,15 @@ extern "C" int e3_sample_entropy(const void* logits, int dtype, int64_t rows, in
     return err == hipSuccess ? E3_OK : E3_ERR_LAUNCH;
 }
 
+extern "C" int e3_read_probe(const void* buf, int64_t bytes, uint32_t* sums_out, void* hip_stream)
+{
+    if (bytes < 0 || (bytes & 15) != 0) return E3_ERR_SHAPE;
+    if (sums_out == nullptr || (buf == nullptr && bytes > 0)) return E3_ERR_NULL;
+    if ((reinterpret_cast<uintptr_t>(buf) & 15u) != 0) return E3_ERR_ALIGN;
+    hipError_t err = e3::launch_read_probe(buf, bytes, sums_out, static_cast<hipStream_t>(hip_stream));
+    return err == hipSuccess ? E3_OK : E3_ERR_LAUNCH;
+}
+
 extern "C" int e3_sample_restricted(const void* logits, int dtype, int64_t rows, int64_t V,
                                     int64_t row_stride, const float* tau_rows, float tau_scalar,
                                     int32_t top_k, float top_p, uint64_t seed, uint64_t row_base,

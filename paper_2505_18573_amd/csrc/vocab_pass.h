@@ -38,6 +38,10 @@ hipError_t launch_sample_restricted(const void* logits, int64_t rows, int64_t V,
                                     uint64_t seed, uint64_t row_base, int32_t* token_out,
                                     float* logp_out, int32_t* kept_out, hipStream_t stream);
 
+// read-bandwidth probe: kReadProbeBlocks xor checksums of `bytes` (multiple of 16) bytes
+constexpr int kReadProbeBlocks = 2048;
+hipError_t launch_read_probe(const void* buf, int64_t bytes, uint32_t* sums, hipStream_t stream);
+
 hipError_t launch_grpo_advantages(const float* rewards, const int32_t* offsets, int32_t num_groups,
                                   int32_t ddof, float eps, float* adv_out, hipStream_t stream);
 

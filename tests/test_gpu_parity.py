@@ -374,3 +374,14 @@ def test_unusable_workspace_falls_back_to_whole_rows():
         assert torch.equal(a, b)
     assert torch.equal(first[0], want[0])
     assert torch.allclose(first[2], want[2], rtol=1e-5, atol=0)
+
+
+def test_read_probe_reads_every_word():
+    g = torch.Generator(device=DEV).manual_seed(41)
+    for n in (0, 4, 4 * 2048 * 256 + 12, 1_000_004):                    # 32-bit words, multiples of 4
+        buf = torch.randint(-2**31, 2**31 - 1, (n,), generator=g, device=DEV, dtype=torch.int64).to(torch.int32)
+        sums = e3.e3_read_probe(buf)
+        torch.cuda.synchronize()
+        want = np.bitwise_xor.reduce(buf.cpu().numpy().view(np.uint32)) if n else 0
+        got = np.bitwise_xor.reduce(sums.cpu().numpy().view(np.uint32))
+        assert int(got) == int(want)
