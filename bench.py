@@ -15,12 +15,14 @@ the 256 MB memory-side cache, so the step rotates over enough distinct logit buf
 that more than 1 GB is touched between two uses of the same buffer.
 
 Prints ONE JSON line.  `roofline` prices the sample kernel's algorithmic bytes against
-the 8 TB/s HBM peak using HIP-event timings taken inside the timed region;
+the 8 TB/s HBM peak using HIP events attached to the kernel's dispatch in every timed step;
+`read_ceiling` is a read-only kernel over the same buffers timed the same way;
 `cpu_baseline` times the CPU oracle on the same workload (reported, not a target).
 """
 from __future__ import annotations
 
 import argparse
+import ctypes
 import json
 import os
 import sys
@@ -41,6 +43,36 @@ BYTES_PER_ROW = V * 2 + 4 + 12
 # what the same counter reads for a device copy of known size (profiles/…hbm_traffic.txt).
 # Valid for the kernel as profiled; set to None when the kernel changes until re-measured.
 MEASURED_TRAFFIC_BYTES = 157_161_480
+
+
+class DispatchEvents:
+    """hipEvent_t pairs that the library attaches to a kernel dispatch (e3_time_next_launch):
+    their difference is the kernel's own execution time, as a profiler reports it."""
+
+    def __init__(self):
+        self.hip = ctypes.CDLL("libamdhip64.so")
+        self.hip.hipEventCreate.argtypes = [ctypes.POINTER(ctypes.c_void_p)]
+        self.hip.hipEventElapsedTime.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.c_void_p,
+                                                 ctypes.c_void_p]
+        self.hip.hipEventDestroy.argtypes = [ctypes.c_void_p]
+
+    def pair(self):
+        a, b = ctypes.c_void_p(), ctypes.c_void_p()
+        if self.hip.hipEventCreate(ctypes.byref(a)) != 0 or self.hip.hipEventCreate(ctypes.byref(b)) != 0:
+            raise RuntimeError("hipEventCreate failed")
+        return a, b
+
+    def elapsed_ms(self, a, b) -> float:
+        ms = ctypes.c_float()
+        rc = self.hip.hipEventElapsedTime(ctypes.byref(ms), a, b)
+        if rc != 0:
+            raise RuntimeError(f"hipEventElapsedTime failed: {rc}")
+        return ms.value
+
+    def destroy(self, pairs):
+        for a, b in pairs:
+            self.hip.hipEventDestroy(a)
+            self.hip.hipEventDestroy(b)
 
 
 def main() -> int:
@@ -103,10 +135,9 @@ def main() -> int:
     stream = torch.cuda.current_stream(dev)
 
     def step(i: int, ev=None):
-        """One cycle of the method.  The order inside a cycle is the loop's own (training
-        pass on the previous rollouts -> scheduler -> next rollouts), rotated so that the
-        sampling call is enqueued while the GPU is still busy: its HIP events then bracket
-        the kernel itself and not the host's launch latency."""
+        """One cycle of the method: advantages, training pass on the previous rollouts, next
+        rollouts, read-back and scheduler.  `ev`: a HIP event pair that the library attaches
+        to the sampling kernel's dispatch (begin and end of its execution)."""
         roll = batches[i % nb]
         train = batches[(i + nb // 2) % nb]
         e3.e3_grpo_advantages(rewards, offsets, 0, 0.0, adv_out=adv)
@@ -114,11 +145,9 @@ def main() -> int:
                               entropy_out=ent_t, entropy_sum_out=hsum, entropy_count_out=hcnt,
                               workspace=ws)
         if ev is not None:
-            ev[0].record(stream)
+            e3.e3_time_next_launch(ev[0].value, ev[1].value)
         e3.e3_sample_entropy(roll.logits, roll.tau_rows, 1.0, seed=99, row_base=i * ROWS,
                              token_out=tok, logp_out=logp_s, entropy_out=ent_s, workspace=ws)
-        if ev is not None:
-            ev[1].record(stream)
         hsum_host.copy_(hsum, non_blocking=True)
         hcnt_host.copy_(hcnt, non_blocking=True)
         stream.synchronize()
@@ -135,18 +164,8 @@ def main() -> int:
         step(i)
     torch.cuda.synchronize()
 
-    # what an empty event pair reads on a busy stream (marker packets are not free)
-    probe = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
-             for _ in range(50)]
-    for a_ev, b_ev in probe:
-        e3.e3_grpo_advantages(rewards, offsets, 0, 0.0, adv_out=adv)
-        a_ev.record(stream)
-        b_ev.record(stream)
-    torch.cuda.synchronize()
-    pair_ms = sorted(x.elapsed_time(y) for x, y in probe)[len(probe) // 2]
-
-    events = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
-              for _ in range(args.steps)]
+    dev_events = DispatchEvents()
+    events = [dev_events.pair() for _ in range(args.steps)]
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for i in range(args.steps):
@@ -154,9 +173,24 @@ def main() -> int:
     torch.cuda.synchronize()
     t1 = time.perf_counter()
 
+    # The same launches bracketed by marker events (torch.cuda.Event pairs recorded on the
+    # stream), for reference: markers are packets of their own and read ~5 us more.
+    markers = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+               for _ in range(50)]
+    for j, (a_ev, b_ev) in enumerate(markers):
+        roll = batches[j % nb]
+        e3.e3_grpo_advantages(rewards, offsets, 0, 0.0, adv_out=adv)
+        a_ev.record(stream)
+        e3.e3_sample_entropy(roll.logits, roll.tau_rows, 1.0, seed=99, row_base=j * ROWS,
+                             token_out=tok, logp_out=logp_s, entropy_out=ent_s, workspace=ws)
+        b_ev.record(stream)
+    torch.cuda.synchronize()
+    marker_ms = sorted(x.elapsed_time(y) for x, y in markers)
+
     ms_per_step = (t1 - t0) * 1e3 / args.steps
     rows_per_s = ROWS * args.steps / (t1 - t0)
-    kern_ms = sorted(a.elapsed_time(b) for a, b in events)
+    kern_ms = sorted(dev_events.elapsed_ms(a, b) for a, b in events)
+    dev_events.destroy(events)
     kern_avg_ms = sum(kern_ms) / len(kern_ms)
     achieved = ROWS * BYTES_PER_ROW / (kern_avg_ms * 1e-3) / 1e9
 
@@ -183,9 +217,10 @@ def main() -> int:
         "sample_kernel": {
             "avg_ms": kern_avg_ms, "median_ms": kern_ms[len(kern_ms) // 2], "min_ms": kern_ms[0],
             "rows_per_s": ROWS / (kern_avg_ms * 1e-3),
-            "timing": "HIP events on the launch stream around e3_sample_entropy, every timed step",
-            "empty_event_pair_ms": pair_ms,
-            "avg_ms_minus_empty_pair": kern_avg_ms - pair_ms,
+            "timing": "HIP events attached to the kernel's dispatch (hipExtLaunchKernel start/stop "
+                      "events via e3_time_next_launch), every timed step",
+            "marker_pair_avg_ms": sum(marker_ms) / len(marker_ms),
+            "marker_pair_note": "the same launch bracketed by two recorded marker events instead",
         },
         "roofline": {
             "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
@@ -195,7 +230,7 @@ def main() -> int:
         "scheduler": {"tau_after": state["tau"], "H_init": state["H_init"]},
     }
 
-    out["read_ceiling"] = read_ceiling_leg(e3, batches, stream, pair_ms)
+    out["read_ceiling"] = read_ceiling_leg(e3, batches, dev_events)
     out["roofline"]["frac_of_read_ceiling"] = achieved / out["read_ceiling"]["GBps"]
     if args.restricted:
         out["restricted_sampling"] = restricted_leg(e3, batches, stream)
@@ -205,28 +240,26 @@ def main() -> int:
     return 0
 
 
-def read_ceiling_leg(e3, batches, stream, pair_ms, reps: int = 50):
+def read_ceiling_leg(e3, batches, dev_events, reps: int = 50):
     """What a pure read of the same logit buffers reaches on this machine, timed exactly like
-    the sample kernel (one HIP event pair per launch on a busy stream, rotating buffers)."""
+    the sample kernel (events attached to the dispatch, back-to-back launches, rotating
+    buffers)."""
     dev = batches[0].logits.device
     sums = torch.empty(e3.binding.E3_READ_PROBE_SUMS, dtype=torch.int32, device=dev)
-    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
-           for _ in range(reps)]
+    evs = [dev_events.pair() for _ in range(reps)]
     for i in range(5 + reps):
         b = batches[i % len(batches)]
         if i >= 5:
-            evs[i - 5][0].record(stream)
+            e3.e3_time_next_launch(evs[i - 5][0].value, evs[i - 5][1].value)
         e3.e3_read_probe(b.logits, sums)
-        if i >= 5:
-            evs[i - 5][1].record(stream)
     torch.cuda.synchronize()
-    ms = sorted(a.elapsed_time(b) for a, b in evs)
+    ms = sorted(dev_events.elapsed_ms(a, b) for a, b in evs)
+    dev_events.destroy(evs)
     avg = sum(ms) / len(ms)
     nbytes = ROWS * V * 2
     return {"kernel": "read_probe_kernel (16-byte non-temporal loads, xor checksum only)",
             "avg_ms": avg, "median_ms": ms[len(ms) // 2], "GBps": nbytes / (avg * 1e-3) / 1e9,
-            "frac_of_hbm_peak": nbytes / (avg * 1e-3) / 1e9 / HBM_PEAK_GBPS,
-            "avg_ms_minus_empty_pair": avg - pair_ms}
+            "frac_of_hbm_peak": nbytes / (avg * 1e-3) / 1e9 / HBM_PEAK_GBPS}
 
 
 def restricted_leg(e3, batches, stream, reps: int = 50):

@@ -111,6 +111,18 @@ int e3_sample_entropy(const void* logits, int dtype, int64_t rows, int64_t V, in
                       void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /*
+ * Measurement hook.  The next e3_sample_entropy / e3_logprob_entropy(_gap) / e3_read_probe
+ * call made by this host thread attaches the two events (hipEvent_t created by the caller with timing
+ * enabled; either may be NULL) to its vocabulary-pass dispatch: `start_event` then holds
+ * the time the kernel began to execute and `stop_event` the time it ended (with a
+ * workspace and a small batch: begin of the first of the two kernels, end of the second),
+ * so hipEventElapsedTime gives the kernel's own duration without the cost of marker
+ * packets recorded around it.  The hook is consumed by that one call; calling it again
+ * before replaces the events; NULL, NULL clears it.  Always returns E3_OK.
+ */
+int e3_time_next_launch(void* start_event, void* stop_event);
+
+/*
  * Diagnostic, for callers that measure: read `bytes` bytes of device memory once, with
  * the access pattern of the vocabulary pass (16-byte non-temporal loads), and write
  * E3_READ_PROBE_SUMS xor checksums (one per workgroup; their xor is the xor of all

@@ -24,7 +24,8 @@ EXPORTS = ("e3_strerror", "e3_workspace_bytes", "e3_sample_entropy", "e3_sample_
            "e3_logprob_entropy",
            "e3_grpo_advantages", "e3_temperature_update", "e3_difficulty_ranks",
            "e3_allocate_budgets", "e3_budget_bounds", "e3_logprob_entropy_gap",
-           "e3_temperature_update_gap", "e3_grpo_objective", "e3_read_probe")
+           "e3_temperature_update_gap", "e3_grpo_objective", "e3_read_probe",
+           "e3_time_next_launch")
 
 _lib: Optional[C.CDLL] = None
 
@@ -54,6 +55,8 @@ def lib() -> C.CDLL:
         L.e3_sample_restricted.argtypes = [vp, C.c_int, i64, i64, i64, vp, f32, i32, f32, u64, u64,
                                            vp, vp, vp, vp]
         L.e3_sample_restricted.restype = C.c_int
+        L.e3_time_next_launch.argtypes = [vp, vp]
+        L.e3_time_next_launch.restype = C.c_int
         L.e3_read_probe.argtypes = [vp, i64, vp, vp]
         L.e3_read_probe.restype = C.c_int
         L.e3_logprob_entropy.argtypes = [vp, C.c_int, i64, i64, i64, vp, vp, vp, f32,
@@ -197,6 +200,11 @@ def e3_sample_restricted(logits: torch.Tensor, tau_rows: Optional[torch.Tensor],
 
 
 E3_READ_PROBE_SUMS = 2048
+
+
+def e3_time_next_launch(start_event: Optional[int], stop_event: Optional[int]) -> None:
+    """start_event / stop_event: hipEvent_t handles as integers (or None)."""
+    lib().e3_time_next_launch(C.c_void_p(start_event), C.c_void_p(stop_event))
 
 
 def e3_read_probe(buf: torch.Tensor, sums_out: Optional[torch.Tensor] = None) -> torch.Tensor:

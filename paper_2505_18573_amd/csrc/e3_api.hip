@@ -74,6 +74,12 @@ extern "C" int e3_sample_entropy(const void* logits, int dtype, int64_t rows, in
     return err == hipSuccess ? E3_OK : E3_ERR_LAUNCH;
 }
 
+extern "C" int e3_time_next_launch(void* start_event, void* stop_event)
+{
+    e3::set_launch_events(static_cast<hipEvent_t>(start_event), static_cast<hipEvent_t>(stop_event));
+    return E3_OK;
+}
+
 extern "C" int e3_read_probe(const void* buf, int64_t bytes, uint32_t* sums_out, void* hip_stream)
 {
     if (bytes < 0 || (bytes & 15) != 0) return E3_ERR_SHAPE;

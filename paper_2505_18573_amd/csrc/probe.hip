@@ -6,6 +6,7 @@
 // be read against what a pure read of the same bytes reaches on the same machine.
 #include "vocab_common.h"
 #include "vocab_pass.h"
+#include <hip/hip_ext.h>
 
 namespace e3 {
 namespace {
@@ -43,8 +44,13 @@ void read_probe_kernel(const u32x4* __restrict__ base, int64_t n16, uint32_t* __
 
 hipError_t launch_read_probe(const void* buf, int64_t bytes, uint32_t* sums, hipStream_t stream)
 {
-    hipLaunchKernelGGL(read_probe_kernel, dim3(kReadProbeBlocks), dim3(kProbeThreads), 0, stream,
-                       static_cast<const u32x4*>(buf), bytes / 16, sums);
+    const LaunchEvents ev = take_launch_events();
+    if (ev.start != nullptr || ev.stop != nullptr)
+        hipExtLaunchKernelGGL(read_probe_kernel, dim3(kReadProbeBlocks), dim3(kProbeThreads), 0u, stream,
+                              ev.start, ev.stop, 0u, static_cast<const u32x4*>(buf), bytes / 16, sums);
+    else
+        hipLaunchKernelGGL(read_probe_kernel, dim3(kReadProbeBlocks), dim3(kProbeThreads), 0, stream,
+                           static_cast<const u32x4*>(buf), bytes / 16, sums);
     return hipGetLastError();
 }
 

@@ -23,6 +23,14 @@ struct VocabPassArgs {
 hipError_t launch_vocab_pass(const VocabPassArgs& a, bool is_bf16, bool sample,
                              void* workspace, size_t workspace_bytes, hipStream_t stream);
 
+// events (nullable) that the next launch_vocab_pass of this host thread attaches to its
+// kernel dispatch(es); consumed by that launch
+void set_launch_events(hipEvent_t start, hipEvent_t stop);
+struct LaunchEvents {
+    hipEvent_t start, stop;
+};
+LaunchEvents take_launch_events();
+
 // upper bound of the workspace the small-batch path can use for this shape (0: none)
 size_t vocab_pass_workspace_bytes(int64_t rows, int64_t V);
 

@@ -25,6 +25,7 @@
 //     while the other waves keep streaming.
 #include "vocab_common.h"
 #include "vocab_pass.h"
+#include <hip/hip_ext.h>
 
 namespace e3 {
 
@@ -527,6 +528,26 @@ void entropy_reduce_kernel(const float* __restrict__ entropy, const uint8_t* __r
 // ---------------------------------------------------------------------------
 constexpr size_t kLdsBudget = 64 * 1024;
 
+// Optional events for the next vocabulary-pass launch of this host thread: `start` gets
+// the time the (first) kernel begins to execute, `stop` the time the (last) kernel ends,
+// taken from the dispatch itself rather than from marker packets around it.
+static thread_local hipEvent_t g_start_event = nullptr;
+static thread_local hipEvent_t g_stop_event = nullptr;
+
+void set_launch_events(hipEvent_t start, hipEvent_t stop)
+{
+    g_start_event = start;
+    g_stop_event = stop;
+}
+
+LaunchEvents take_launch_events()
+{
+    LaunchEvents e{g_start_event, g_stop_event};
+    g_start_event = nullptr;
+    g_stop_event = nullptr;
+    return e;
+}
+
 // Rows per workgroup.  At least enough items that the ticket queue can balance the
 // waves (two per wave), at least two rows, and the noise table must fit LDS
 // (0 = does not fit).  Beyond that minimum, a workgroup of this size occupies a compute
@@ -577,8 +598,14 @@ static hipError_t launch_groups(const VocabPassArgs& a, hipStream_t stream)
     const int nst = (int)((a.V + kSuperCols - 1) / kSuperCols);
     const size_t lds = lds_bytes<kWaves>(rpb, nst, kSample);
     const unsigned blocks = (unsigned)((a.rows + rpb - 1) / rpb);
-    hipLaunchKernelGGL((vocab_pass_kernel<Chunk, kSample, kWaves, Chunk::kAhead>),
-                       dim3(blocks), dim3(kWaves * 64), lds, stream, a, rpb);
+    const LaunchEvents ev = take_launch_events();
+    if (ev.start != nullptr || ev.stop != nullptr)
+        hipExtLaunchKernelGGL((vocab_pass_kernel<Chunk, kSample, kWaves, Chunk::kAhead>),
+                              dim3(blocks), dim3(kWaves * 64), (uint32_t)lds, stream, ev.start, ev.stop, 0u,
+                              a, rpb);
+    else
+        hipLaunchKernelGGL((vocab_pass_kernel<Chunk, kSample, kWaves, Chunk::kAhead>),
+                           dim3(blocks), dim3(kWaves * 64), lds, stream, a, rpb);
     return hipGetLastError();
 }
 
@@ -631,12 +658,22 @@ template <typename Chunk, bool kSample>
 static hipError_t launch_split(const VocabPassArgs& a, RowPartial* ws, SplitPlan plan, hipStream_t stream)
 {
     const unsigned blocks = (unsigned)(a.rows * plan.nslots);
-    hipLaunchKernelGGL((vocab_split_kernel<Chunk, kSample>), dim3(blocks), dim3(64), 0, stream,
-                       a, ws, plan.nslots);
+    const LaunchEvents ev = take_launch_events();
+    const RowPartial* parts = ws;
+    if (ev.start != nullptr)
+        hipExtLaunchKernelGGL((vocab_split_kernel<Chunk, kSample>), dim3(blocks), dim3(64), 0u, stream,
+                              ev.start, (hipEvent_t) nullptr, 0u, a, ws, plan.nslots);
+    else
+        hipLaunchKernelGGL((vocab_split_kernel<Chunk, kSample>), dim3(blocks), dim3(64), 0, stream,
+                           a, ws, plan.nslots);
     hipError_t err = hipGetLastError();
     if (err != hipSuccess) return err;
-    hipLaunchKernelGGL((row_finish_kernel<Chunk, kSample>), dim3((unsigned)a.rows), dim3(64), 0, stream,
-                       a, ws, plan.nslots);
+    if (ev.stop != nullptr)
+        hipExtLaunchKernelGGL((row_finish_kernel<Chunk, kSample>), dim3((unsigned)a.rows), dim3(64), 0u,
+                              stream, (hipEvent_t) nullptr, ev.stop, 0u, a, parts, plan.nslots);
+    else
+        hipLaunchKernelGGL((row_finish_kernel<Chunk, kSample>), dim3((unsigned)a.rows), dim3(64), 0, stream,
+                           a, parts, plan.nslots);
     return hipGetLastError();
 }
 

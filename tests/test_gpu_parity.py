@@ -385,3 +385,30 @@ def test_read_probe_reads_every_word():
         want = np.bitwise_xor.reduce(buf.cpu().numpy().view(np.uint32)) if n else 0
         got = np.bitwise_xor.reduce(sums.cpu().numpy().view(np.uint32))
         assert int(got) == int(want)
+
+
+def test_dispatch_events_time_the_kernel_and_change_nothing():
+    import ctypes
+    hip = ctypes.CDLL("libamdhip64.so")
+    hip.hipEventCreate.argtypes = [ctypes.POINTER(ctypes.c_void_p)]
+    hip.hipEventElapsedTime.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.c_void_p, ctypes.c_void_p]
+    hip.hipEventDestroy.argtypes = [ctypes.c_void_p]
+    g = torch.Generator(device=DEV).manual_seed(51)
+    for rows in (6, 700):                                   # both launch paths
+        lg = (torch.randn((rows, 30_000), generator=g, device=DEV) * 3).to(torch.bfloat16)
+        want = e3.e3_sample_entropy(lg, None, 1.0, 3, 0)
+        a, b = ctypes.c_void_p(), ctypes.c_void_p()
+        assert hip.hipEventCreate(ctypes.byref(a)) == 0 and hip.hipEventCreate(ctypes.byref(b)) == 0
+        e3.e3_time_next_launch(a.value, b.value)
+        got = e3.e3_sample_entropy(lg, None, 1.0, 3, 0)
+        torch.cuda.synchronize()
+        ms = ctypes.c_float()
+        assert hip.hipEventElapsedTime(ctypes.byref(ms), a, b) == 0
+        assert 0.0 < ms.value < 50.0, ms.value
+        for x, y in zip(got, want):
+            assert torch.equal(x, y)
+        again = e3.e3_sample_entropy(lg, None, 1.0, 3, 0)   # the hook was consumed
+        torch.cuda.synchronize()
+        assert torch.equal(again[0], want[0])
+        hip.hipEventDestroy(a)
+        hip.hipEventDestroy(b)
