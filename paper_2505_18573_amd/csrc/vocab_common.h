@@ -170,8 +170,9 @@ __device__ __forceinline__ void philox4x32_10(uint32_t c0, uint32_t c1, uint32_t
     constexpr uint32_t MA = 0xD2511F53u, MB = 0xCD9E8D57u;
 #pragma unroll
     for (int r = 0; r < 10; ++r) {
-        uint32_t ha = __umulhi(MA, c0), la = MA * c0;
-        uint32_t hb = __umulhi(MB, c2), lb = MB * c2;
+        const uint64_t pa = (uint64_t)MA * c0, pb = (uint64_t)MB * c2;   // one v_mad_u64_u32 each
+        const uint32_t ha = (uint32_t)(pa >> 32), la = (uint32_t)pa;
+        const uint32_t hb = (uint32_t)(pb >> 32), lb = (uint32_t)pb;
         uint32_t n0 = hb ^ c1 ^ k0;
         uint32_t n2 = ha ^ c3 ^ k1;
         c0 = n0; c1 = lb; c2 = n2; c3 = la;

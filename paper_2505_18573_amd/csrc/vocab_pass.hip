@@ -95,6 +95,7 @@ __device__ __forceinline__ void finish_row(const VocabPassArgs& a, int64_t row,
     // reference by exact scaling), so that the columns of the winning tile are
     // requested before the fp64 merge below and arrive while it runs.
     float cz[4] = {kAbsent, kAbsent, kAbsent, kAbsent};
+    float inv_e2[4] = {0.0f, 0.0f, 0.0f, 0.0f};
     uint32_t w[4] = {0u, 0u, 0u, 0u};
     int64_t col0 = 0;
     if (kSample) {
@@ -109,6 +110,8 @@ __device__ __forceinline__ void finish_row(const VocabPassArgs& a, int64_t row,
         const uint64_t grow = a.row_base + (uint64_t)row;
         philox4x32_10((uint32_t)(col0 >> 2), (uint32_t)grow, (uint32_t)(grow >> 32), 2u,
                       (uint32_t)a.seed, (uint32_t)(a.seed >> 32), w);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) inv_e2[j] = 1.0f / exp_variate(w[j]);   // while the columns arrive
     }
 
     // Row sums in fp64.
@@ -144,7 +147,7 @@ __device__ __forceinline__ void finish_row(const VocabPassArgs& a, int64_t row,
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             const bool ok = lane < 32 && col0 + j < V;
-            const float q = __builtin_amdgcn_exp2f((cz[j] - zmax) * c) / exp_variate(w[j]);
+            const float q = __builtin_amdgcn_exp2f((cz[j] - zmax) * c) * inv_e2[j];
             cb = better(cb, Cand{ok ? q : -1.0f, ok ? (int)(col0 + j) : 0x7FFFFFFF});
         }
         cb = wave_best(cb);
