@@ -412,3 +412,33 @@ def test_dispatch_events_time_the_kernel_and_change_nothing():
         assert torch.equal(again[0], want[0])
         hip.hipEventDestroy(a)
         hip.hipEventDestroy(b)
+
+
+def _random_cases(n, seed):
+    rng = np.random.default_rng(seed)
+    cases = []
+    for i in range(n):
+        V = int(rng.choice([rng.integers(1, 64), rng.integers(64, 9000), rng.integers(9000, 40_000),
+                            8192 * rng.integers(1, 5), 8192 * rng.integers(1, 5) + 8 * rng.integers(1, 1023)]))
+        rows = int(rng.choice([1, 2, 3, rng.integers(4, 40), rng.integers(40, 700)]))
+        rows = max(1, min(rows, 4_000_000 // V + 1))
+        cases.append((i, V, rows, bool(rng.integers(0, 2)), float(rng.choice([0.05, 0.5, 1.0, 1.7, 30.0])),
+                      float(rng.choice([0.5, 3.0, 12.0]))))
+    return cases
+
+
+@pytest.mark.parametrize("i,V,rows,bf16,tau,sigma", _random_cases(28, 2024))
+def test_seeded_random_shapes(i, V, rows, bf16, tau, sigma):
+    """A fixed list of pseudo-random shapes, temperatures and logit scales through both
+    calls and both launch paths."""
+    g = torch.Generator(device=DEV).manual_seed(1000 + i)
+    dtype = torch.bfloat16 if bf16 else torch.float32
+    esz = 2 if bf16 else 4
+    pitch = -(-V * esz // 16) * 16 // esz + (16 // esz) * (i % 3)
+    store = (torch.randn((rows, pitch), generator=g, device=DEV) * sigma).to(dtype)
+    logits = store[:, :V]
+    tau_rows = None if i % 2 else (tau * (0.5 + torch.rand(rows, generator=g, device=DEV))).float()
+    check_sample(logits, tau_rows, tau, seed=i, row_base=i << 33, label=f"case {i}: {rows}x{V} {dtype} tau={tau}")
+    tgt = torch.randint(0, V, (rows,), generator=g, device=DEV).to(torch.int32)
+    mask = (torch.rand(rows, generator=g, device=DEV) < 0.7).to(torch.uint8) if i % 4 == 0 else None
+    check_logprob(logits, tgt, mask, tau_rows, tau, f"case {i} logprob")

@@ -130,3 +130,26 @@ def test_argument_checks_need_no_gpu():
     assert call(tau=0.0) == -5
     assert call(tok=None) == -1
     assert L.e3_sample_restricted(None, 1, 0, 64, 64, None, 1.0, 5, 0.9, 1, 0, None, None, None, None) == 0
+
+
+def _random_cases(n, seed):
+    rng = np.random.default_rng(seed)
+    out = []
+    for i in range(n):
+        V = int(rng.choice([rng.integers(1, 100), rng.integers(100, 9000), rng.integers(9000, 60_000)]))
+        rows = int(rng.integers(1, 12))
+        k = int(rng.choice([0, 1, 2, rng.integers(3, 200), rng.integers(1, V + 2), V // 2 + 1]))
+        p = float(rng.choice([1.0, 0.999, 0.9, 0.5, 0.1, 1e-4]))
+        out.append((i, V, rows, k, p, float(rng.choice([0.1, 1.0, 4.0, 60.0])), float(rng.choice([0.3, 3.0, 10.0])),
+                    float(rng.choice([0.0, 0.0, -8.0, 8.0]))))
+    return out
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("i,V,rows,k,p,tau,sigma,shift", _random_cases(32, 77))
+def test_seeded_random_settings(i, V, rows, k, p, tau, sigma, shift):
+    g = torch.Generator(device=DEV).manual_seed(500 + i)
+    pitch = -(-V // 8) * 8 + 8 * (i % 2)
+    lg = (torch.randn((rows, pitch), generator=g, device=DEV) * sigma + shift).to(torch.bfloat16)[:, :V]
+    tau_rows = None if i % 2 else (tau * (0.5 + torch.rand(rows, generator=g, device=DEV))).float()
+    check(lg, tau_rows, tau, k, p, seed=i, row_base=i << 20, label=f"case {i}: {rows}x{V} k={k} p={p} tau={tau}")
