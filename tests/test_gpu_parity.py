@@ -1,7 +1,7 @@
 """Parity of the HIP library against the CPU oracle, element by element, on the same
 seeded inputs (needs a GPU; everything goes through the C ABI).
 
-Tolerances (derived in the design doc):
+Tolerances (each follows from the arithmetic stated with it):
   * tokens: identical, except rows the oracle flags as near-ties (top-two perturbed
     scores within 1e-5 relative at either level); the mismatch count is printed;
   * entropy and log-prob: |x - ref| <= 1e-4 * max(|ref|, 1e-6)  (1e-4 relative; the
