@@ -316,7 +316,10 @@ void vocab_pass_kernel(VocabPassArgs a, int rpb)
             RowPartial p;
             p.S = Sw; p.W = Ww; p.rc = s.rc; p.top = s.top; p.q = wb.q; p.tile = wb.idx;
             parts[r * (kWaves + 1) + slot] = p;
-            before = atomicAdd(&done[r], (uint32_t)n_items);      // same wave: after the write
+            // LDS executes one wave's operations in order; keep the compiler from moving
+            // the write below the counter update (a fence would also drain the loads in flight)
+            asm volatile("" ::: "memory");
+            before = atomicAdd(&done[r], (uint32_t)n_items);
         }
         before = __builtin_amdgcn_readfirstlane(before);
         if ((int)before + n_items == nst)
