@@ -266,7 +266,8 @@ def read_ceiling_leg(e3, batches, dev_events, reps: int = 50):
     dev_events.destroy(evs)
     avg = sum(ms) / len(ms)
     nbytes = ROWS * V * 2
-    return {"kernel": "read_probe_kernel (16-byte non-temporal loads, xor checksum only)",
+    return {"kernel": "read_probe_kernel (16-byte non-temporal loads, 8-wave workgroups over contiguous "
+                      "16-KiB runs, xor checksum only)",
             "avg_ms": avg, "median_ms": ms[len(ms) // 2], "GBps": nbytes / (avg * 1e-3) / 1e9,
             "frac_of_hbm_peak": nbytes / (avg * 1e-3) / 1e9 / HBM_PEAK_GBPS}
 

@@ -124,12 +124,14 @@ int e3_time_next_launch(void* start_event, void* stop_event);
 
 /*
  * Diagnostic, for callers that measure: read `bytes` bytes of device memory once, with
- * the access pattern of the vocabulary pass (16-byte non-temporal loads), and write
- * E3_READ_PROBE_SUMS xor checksums (one per workgroup; their xor is the xor of all
- * 32-bit words of the buffer) to sums_out [E3_READ_PROBE_SUMS] uint32, device.  It performs
- * none of the method's arithmetic: timing it on the same buffers gives the read rate that
- * the kernels' achieved GB/s can be compared with.  bytes must be a multiple of 16
- * (E3_ERR_SHAPE) and buf 16-byte aligned (E3_ERR_ALIGN); bytes == 0 writes zeros.
+ * the access pattern of the vocabulary pass (16-byte non-temporal loads, eight-wave
+ * workgroups streaming contiguous 16-KiB runs), and write E3_READ_PROBE_SUMS xor
+ * checksums (one per workgroup, unused slots zero; their xor is the xor of all 32-bit
+ * words of the buffer) to sums_out [E3_READ_PROBE_SUMS] uint32, device.  It performs none
+ * of the method's arithmetic: timing it on the same buffers gives the read rate that the
+ * kernels' achieved GB/s can be compared with (meant for buffers of a hundred MB and more;
+ * small buffers get few workgroups).  bytes must be a multiple of 16 (E3_ERR_SHAPE) and
+ * buf 16-byte aligned (E3_ERR_ALIGN); bytes == 0 writes zeros.
  */
 #define E3_READ_PROBE_SUMS 2048
 int e3_read_probe(const void* buf, int64_t bytes, uint32_t* sums_out, void* hip_stream);

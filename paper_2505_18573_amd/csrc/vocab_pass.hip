@@ -229,7 +229,7 @@ template <typename Chunk, bool kSample, int kWaves, int kAhead>
 __global__ __launch_bounds__(kWaves * 64)
 void vocab_pass_kernel(VocabPassArgs a, int rpb)
 {
-    static_assert(kAhead >= 1 && kAhead < kDepth, "the follow-up item must be known mid-item");
+    static_assert(kAhead >= 1 && kAhead <= kDepth && kDepth % kAhead == 0, "the register ring must close over a super-tile");
     extern __shared__ __align__(16) char smem[];
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
