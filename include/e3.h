@@ -45,7 +45,7 @@ typedef enum { E3_F32 = 0, E3_BF16 = 1 } e3_dtype;
  */
 #define E3_TILE_CHUNK 8
 #define E3_TILE_LANES 64
-#define E3_TILE_DEPTH 16
+#define E3_TILE_DEPTH 8
 
 /* Static, never-freed description of a status code (host). */
 const char* e3_strerror(int status);
@@ -100,7 +100,7 @@ size_t e3_workspace_bytes(int64_t rows, int64_t V);
  *             logp_out and entropy_out may be NULL.
  * workspace   device scratch of workspace_bytes bytes, or NULL (see
  *             e3_workspace_bytes); contents on entry are ignored.
- * V           at most 2,080,768 columns (per-workgroup tables must fit LDS),
+ * V           at most 1,040,384 columns (per-workgroup tables must fit LDS),
  *             else E3_ERR_SHAPE.
  * rows == 0 is a no-op.  fp32 accumulation per lane, fp64 merges.
  */

@@ -17,8 +17,8 @@ from . import build as _build
 F32, BF16 = 0, 1
 
 # Column partition of the two-level sampler that the HIP library fixes:
-# chunks of 8 columns dealt round-robin to 64 slots, 16 chunks of a slot per tile.
-LIB_PARTITION = (8, 64, 16)
+# chunks of 8 columns dealt round-robin to 64 slots, 8 chunks of a slot per tile.
+LIB_PARTITION = (8, 64, 8)
 
 _lib = None
 

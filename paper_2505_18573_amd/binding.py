@@ -18,7 +18,7 @@ LIB_PATH = os.path.join(HERE, "libe3.so")
 
 E3_F32, E3_BF16 = 0, 1
 E3_OK = 0
-E3_TILE_CHUNK, E3_TILE_LANES, E3_TILE_DEPTH = 8, 64, 16
+E3_TILE_CHUNK, E3_TILE_LANES, E3_TILE_DEPTH = 8, 64, 8
 
 EXPORTS = ("e3_strerror", "e3_workspace_bytes", "e3_sample_entropy", "e3_sample_restricted",
            "e3_logprob_entropy",

@@ -13,7 +13,7 @@ int check_logits(const void* logits, int dtype, int64_t rows, int64_t V, int64_t
     if (dtype != E3_F32 && dtype != E3_BF16) return E3_ERR_DTYPE;
     if (rows < 0 || V < 1 || row_stride < V) return E3_ERR_SHAPE;
     if (V > (int64_t)0x7FFFFFFF - 8192 || rows > (int64_t)0x7FFFFFFF) return E3_ERR_SHAPE;
-    if (!e3::vocab_pass_fits(V)) return E3_ERR_SHAPE;      // beyond ~2M columns
+    if (!e3::vocab_pass_fits(V)) return E3_ERR_SHAPE;      // beyond ~1M columns
     if (rows == 0) return E3_OK;
     if (logits == nullptr) return E3_ERR_NULL;
     const int64_t esz = dtype == E3_F32 ? 4 : 2;

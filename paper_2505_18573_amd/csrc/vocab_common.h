@@ -16,27 +16,24 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 // Tunables (overridable at compile time for experiments).
 #ifndef E3_AHEAD_BF16
-#define E3_AHEAD_BF16 8      // 8 sweeps x 1 KiB per wave in flight (must stay below 16)
+#define E3_AHEAD_BF16 4      // 4 sweeps x 1 KiB per wave in flight (must divide the tile depth)
 #endif
 #ifndef E3_AHEAD_F32
-#define E3_AHEAD_F32 8       // 8 sweeps x 2 KiB per wave in flight
+#define E3_AHEAD_F32 4       // 4 sweeps x 2 KiB per wave in flight
 #endif
 #ifndef E3_NT_LOADS
 #define E3_NT_LOADS 1        // stream the logits with non-temporal loads
 #endif
-#ifndef E3_ROUND_AWARE_ROWS
-#define E3_ROUND_AWARE_ROWS 1     // size row-block workgroups for whole rounds over the CUs
-#endif
 #ifndef E3_SPLIT_BELOW_NUM        // small-batch path while row-block workgroups <= CUs * NUM / DEN
-#define E3_SPLIT_BELOW_NUM 5
+#define E3_SPLIT_BELOW_NUM 3
 #define E3_SPLIT_BELOW_DEN 8
 #endif
 
 constexpr int kChunk = 8;                       // columns per lane per sweep
 constexpr int kLanes = 64;                      // lanes = tiles per super-tile
-constexpr int kDepth = 16;                      // sweeps per super-tile
+constexpr int kDepth = 8;                       // sweeps per super-tile
 constexpr int kSweepCols = kChunk * kLanes;     // 512
-constexpr int kSuperCols = kSweepCols * kDepth; // 8192
+constexpr int kSuperCols = kSweepCols * kDepth; // 4096
 constexpr double kLog2e = 1.4426950408889634074;
 constexpr float kLog2eF = 1.44269504088896340736f;
 constexpr double kLn2 = 0.69314718055994530942;

@@ -10,10 +10,10 @@
 // a sampler; the two-level Gumbel-max used here is specified in include/e3.h.
 //
 // Work decomposition (wave = 64 lanes):
-//   * a row is cut into super-tiles of 8192 columns; one wave streams a whole
-//     super-tile as 16 sweeps of 64 lanes x 8 columns (16 bytes of bf16 per lane),
+//   * a row is cut into super-tiles of 4096 columns; one wave streams a whole
+//     super-tile as 8 sweeps of 64 lanes x 8 columns (16 bytes of bf16 per lane),
 //     so every load instruction of a wave covers 1 KiB of contiguous memory, and the
-//     16 chunks one lane sees are exactly one sampler tile;
+//     8 chunks one lane sees are exactly one sampler tile;
 //   * a workgroup of 8 waves owns a few whole rows; the super-tiles of those rows are
 //     work items that the waves draw from a ticket counter in LDS, so a wave that is
 //     served faster by the memory system simply takes more of them, and a wave keeps
@@ -101,12 +101,12 @@ __device__ __forceinline__ void finish_row(const VocabPassArgs& a, int64_t row,
     if (kSample) {
         const Cand win = wave_best(Cand{live ? ldexpf(p.q, sh) : -1.0f, p.tile});
         const int wst = win.idx / kLanes, wslot = win.idx % kLanes;
-        // 32 lanes x 4 consecutive columns cover the tile
+        // 2 * kDepth lanes x 4 consecutive columns cover the tile
         col0 = (int64_t)wst * kSuperCols + (int64_t)(lane >> 1) * kSweepCols
              + (int64_t)wslot * kChunk + (lane & 1) * 4;
 #pragma unroll
         for (int j = 0; j < 4; ++j)
-            if (lane < 32 && col0 + j < V) cz[j] = Chunk::load_one(rowp, col0 + j);
+            if (lane < 2 * kDepth && col0 + j < V) cz[j] = Chunk::load_one(rowp, col0 + j);
         const uint64_t grow = a.row_base + (uint64_t)row;
         philox4x32_10((uint32_t)(col0 >> 2), (uint32_t)grow, (uint32_t)(grow >> 32), 2u,
                       (uint32_t)a.seed, (uint32_t)(a.seed >> 32), w);
@@ -146,7 +146,7 @@ __device__ __forceinline__ void finish_row(const VocabPassArgs& a, int64_t row,
         Cand cb{-1.0f, 0x7FFFFFFF};
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
-            const bool ok = lane < 32 && col0 + j < V;
+            const bool ok = lane < 2 * kDepth && col0 + j < V;
             const float q = __builtin_amdgcn_exp2f((cz[j] - zmax) * c) * inv_e2[j];
             cb = better(cb, Cand{ok ? q : -1.0f, ok ? (int)(col0 + j) : 0x7FFFFFFF});
         }
@@ -187,7 +187,7 @@ __device__ __forceinline__ void fresh(LaneState& s)
     s.best = Cand{-1.0f, 0};
 }
 
-// A row's incomplete last super-tile: sweeps in two halves of 8, the guarded loads of a
+// A row's incomplete last super-tile: sweeps in two halves, the guarded loads of a
 // half all issued before the first is used; columns past V count as absent.  Returns
 // whether this lane's tile holds any column.
 template <typename Chunk>
@@ -554,34 +554,22 @@ LaunchEvents take_launch_events()
     return e;
 }
 
-// Rows per workgroup.  At least enough items that the ticket queue can balance the
-// waves (two per wave), at least two rows, and the noise table must fit LDS
-// (0 = does not fit).  Beyond that minimum, a workgroup of this size occupies a compute
-// unit alone, so the launch runs in ceil(groups / CUs) rounds of rpb rows each: among
-// the sizes that fit, take the one with the fewest row-rounds (768 rows on 256 CUs:
-// 3 rows in one round instead of 2 rows in two), and on a tie the smallest (measured:
-// consecutive rounds of small workgroups overlap their ends and starts on a compute
-// unit, one long round does not).
+// Rows per workgroup: enough items that the ticket queue can balance the waves (two
+// per wave; one row of 38 super-tiles at V = 151,936), and the noise table must fit LDS
+// (0 = does not fit).  Two 8-wave workgroups are resident per compute unit; what exceeds
+// that is handed out by the hardware dispatcher as workgroups finish.
 template <int kWaves>
-static int rows_per_group(int64_t rows, int64_t V, bool sample, int cus)
+static int rows_per_group(int64_t V, bool sample)
 {
     const int nst = (int)((V + kSuperCols - 1) / kSuperCols);
     int rpb = (2 * kWaves + nst - 1) / nst;
-    if (rpb < 2) rpb = 2;
+    if (rpb < 1) rpb = 1;
     while (rpb > 1 && lds_bytes<kWaves>(rpb, nst, sample) > kLdsBudget) --rpb;
     if (lds_bytes<kWaves>(rpb, nst, sample) > kLdsBudget) return 0;
-#if E3_ROUND_AWARE_ROWS
-    if (kWaves != 8) return rpb;      // smaller workgroups share a compute unit: no rounds
-    auto cost = [&](int r) { return ((rows + r - 1) / r + cus - 1) / cus * r; };
-    int best = rpb;
-    for (int r = rpb + 1; r <= 4 * rpb && lds_bytes<kWaves>(r, nst, sample) <= kLdsBudget; ++r)
-        if (cost(r) < cost(best)) best = r;
-    rpb = best;
-#endif
     return rpb;
 }
 
-bool vocab_pass_fits(int64_t V) { return rows_per_group<8>(1, V, true, 1) > 0 && rows_per_group<4>(1, V, true, 1) > 0; }
+bool vocab_pass_fits(int64_t V) { return rows_per_group<8>(V, true) > 0 && rows_per_group<4>(V, true) > 0; }
 
 static int compute_units()
 {
@@ -599,7 +587,7 @@ static int compute_units()
 template <typename Chunk, bool kSample, int kWaves>
 static hipError_t launch_groups(const VocabPassArgs& a, hipStream_t stream)
 {
-    const int rpb = rows_per_group<kWaves>(a.rows, a.V, kSample, compute_units());
+    const int rpb = rows_per_group<kWaves>(a.V, kSample);
     if (rpb == 0) return hipErrorInvalidValue;
     const int nst = (int)((a.V + kSuperCols - 1) / kSuperCols);
     const size_t lds = lds_bytes<kWaves>(rpb, nst, kSample);
@@ -615,19 +603,18 @@ static hipError_t launch_groups(const VocabPassArgs& a, hipStream_t stream)
     return hipGetLastError();
 }
 
-// Eight waves per workgroup while the whole batch is at most four workgroups per
-// compute unit (one CU then holds its share in one or two groups whose waves balance
-// each other through the ticket queue); four waves per workgroup beyond that, where
-// the hardware dispatcher balances across many small groups (measured crossover on
-// MI355X: between 2048 and 4096 rows of 151,936 bf16 columns).
+// Eight waves per workgroup while the whole batch is at most eight workgroups per
+// compute unit; four waves per workgroup beyond that, where the hardware dispatcher
+// balances across many small groups (measured crossover on MI355X: between 2048 and
+// 4096 rows of 151,936 bf16 columns).
 template <typename Chunk, bool kSample>
 static hipError_t launch_for(const VocabPassArgs& a, hipStream_t stream)
 {
 #ifdef E3_FORCE_WAVES
     return launch_groups<Chunk, kSample, E3_FORCE_WAVES>(a, stream);
 #else
-    const int rpb8 = rows_per_group<8>(1, a.V, kSample, 1);       // the minimum size
-    if (rpb8 > 0 && (a.rows + rpb8 - 1) / rpb8 <= 4 * (int64_t)compute_units())
+    const int rpb8 = rows_per_group<8>(a.V, kSample);
+    if (rpb8 > 0 && (a.rows + rpb8 - 1) / rpb8 <= 8 * (int64_t)compute_units())
         return launch_groups<Chunk, kSample, 8>(a, stream);
     return launch_groups<Chunk, kSample, 4>(a, stream);
 #endif
@@ -688,7 +675,7 @@ hipError_t launch_vocab_pass(const VocabPassArgs& a, bool is_bf16, bool sample,
 {
     if (a.rows == 0) return hipSuccess;
     const int cus = compute_units();
-    const int rpb8 = rows_per_group<8>(1, a.V, sample, 1);            // the minimum size
+    const int rpb8 = rows_per_group<8>(a.V, sample);
 #ifdef E3_SPLIT_ALWAYS
     const bool few = a.rows <= kSplitMaxRows;
 #else

@@ -42,8 +42,8 @@ def test_strerror_and_workspace():
         assert e3.e3_strerror(code) not in ("ok", "unknown status")
     assert e3.e3_strerror(-99) == "unknown status"
     assert e3.e3_workspace_bytes(0, 1) == 0
-    # 32 bytes per run of columns, at most one run per super-tile of 8192 columns and 64 per row
-    assert e3.e3_workspace_bytes(512, 151_936) == 512 * 19 * 32
+    # 32 bytes per run of columns, at most one run per super-tile of 4096 columns and 64 per row
+    assert e3.e3_workspace_bytes(512, 151_936) == 512 * 38 * 32
     assert e3.e3_workspace_bytes(3, 1024) == 3 * 1 * 32
     assert e3.e3_workspace_bytes(1024, 2_000_000) == 1024 * 64 * 32
     assert e3.e3_workspace_bytes(1025, 151_936) == 0         # large batches need none
@@ -141,3 +141,9 @@ def test_temperature_update_pins_and_errors():
     assert L.e3_temperature_update(0.0, 0.2, 0.2, 1000, 0, -1, 0, 1.0, 0.0, float("inf"),
                                    C.addressof(out), None) == -5
     assert out.value == 123.0                                  # untouched on error
+
+
+def test_widest_row_that_fits_the_lds_tables():
+    # 254 super-tiles of 4096 columns: the level-1 noise table of one row fills the LDS budget
+    assert _sample(V=1_040_384 + 8, stride=1_040_384 + 8) == -2          # E3_ERR_SHAPE
+    assert _sample(V=1_040_384, stride=1_040_384, logits=None) == -1     # shape accepted: next check (NULL)

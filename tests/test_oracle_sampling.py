@@ -52,14 +52,14 @@ def test_matches_restatement_on_tiny_rows(partition):
 
 def test_library_partition_shape():
     chunk, lanes, depth = o.LIB_PARTITION
-    assert (chunk, lanes, depth) == (8, 64, 16)
-    assert o.num_tiles(151_936) == 19 * 64 and o.num_tiles(1024) == 64 and o.num_tiles(8192) == 64
-    assert o.num_tiles(8193) == 128
+    assert (chunk, lanes, depth) == (8, 64, 8)
+    assert o.num_tiles(151_936) == 38 * 64 and o.num_tiles(1024) == 64 and o.num_tiles(4096) == 64
+    assert o.num_tiles(4097) == 128
     # columns 0..7 -> tile 0, 8..15 -> tile 1, ..., 504..511 -> tile 63, 512.. wraps to tile 0
-    assert [o.tile_of(c) for c in (0, 7, 8, 511, 512, 519, 8191, 8192, 8200)] == \
+    assert [o.tile_of(c) for c in (0, 7, 8, 511, 512, 519, 4095, 4096, 4104)] == \
         [0, 0, 1, 63, 0, 0, 63, 64, 65]
-    sizes = np.bincount([o.tile_of(c) for c in range(8192 + 100)], minlength=128)
-    assert (sizes[:64] == 128).all() and sizes[64:76].tolist() == [8] * 12 and sizes[76] == 4
+    sizes = np.bincount([o.tile_of(c) for c in range(4096 + 100)], minlength=128)
+    assert (sizes[:64] == 64).all() and sizes[64:76].tolist() == [8] * 12 and sizes[76] == 4
 
 
 def _freq_test(z, tau, partition, draws, seed):
