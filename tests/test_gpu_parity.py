@@ -442,3 +442,14 @@ def test_seeded_random_shapes(i, V, rows, bf16, tau, sigma):
     tgt = torch.randint(0, V, (rows,), generator=g, device=DEV).to(torch.int32)
     mask = (torch.rand(rows, generator=g, device=DEV) < 0.7).to(torch.uint8) if i % 4 == 0 else None
     check_logprob(logits, tgt, mask, tau_rows, tau, f"case {i} logprob")
+
+
+def test_batch_between_resident_rounds_uses_small_workgroups():
+    # 600 rows of 17 super-tiles: more than the 512 eight-wave workgroups resident at once on
+    # 256 compute units, less than 80 % of two rounds -> the four-wave launch shape
+    g = torch.Generator(device=DEV).manual_seed(61)
+    lg = (torch.randn((600, 16 * 4096 + 8), generator=g, device=DEV) * 3).to(torch.bfloat16)
+    tau = (0.6 + 0.8 * torch.rand(600, generator=g, device=DEV)).float()
+    check_sample(lg, tau, 1.0, seed=12, row_base=5, label="600 x 65544")
+    tgt = torch.randint(0, lg.shape[1], (600,), generator=g, device=DEV).to(torch.int32)
+    check_logprob(lg, tgt, None, tau, 1.0, "600 x 65544 logprob")
