@@ -258,7 +258,7 @@ __device__ __forceinline__ RaceBest race_window(const uint32_t* hist, bool hi, i
         const int sel = bits & 3;
         const uint32_t word = sel == 0 ? w4[0] : sel == 1 ? w4[1] : sel == 2 ? w4[2] : w4[3];
         const float z = __uint_as_float((uint32_t)bits << 16);
-        const float q = (float)n * __builtin_amdgcn_exp2f((z - z1f) * c) / exp_variate(word);
+        const float q = (float)n * __builtin_amdgcn_exp2f((z - z1f) * c) * inv_exp_variate(word);
         // a thread meets its bins in falling value order: `>` keeps the higher level on ties
         if ((double)q > mine.q) { mine.q = (double)q; mine.bits = bits; mine.n = (int)n; }
     }

@@ -180,7 +180,10 @@ __device__ __forceinline__ void philox4x32_10(uint32_t c0, uint32_t c1, uint32_t
 
 // E = -ln(u), u = ((word >> 9) + 1/2) 2^-23.  u and d = 1 - u are exact in fp32.
 // Close to u = 1 the logarithm is taken from the series -ln(1-d) = sum d^k / k,
-// which keeps full relative accuracy where log(u) itself would cancel.
+// which keeps full relative accuracy where log(u) itself would cancel; elsewhere it is
+// the hardware log2 (1 ulp) times ln 2.  inv_exp_variate is 1 / E through the hardware
+// reciprocal (1 ulp): the sampler's scores carry ~3e-7 relative error from these two,
+// far inside the 1e-5 near-tie margin.
 __device__ __forceinline__ float exp_variate(uint32_t word)
 {
     float k = (float)(word >> 9);
@@ -188,8 +191,13 @@ __device__ __forceinline__ float exp_variate(uint32_t word)
     float d = 1.0f - u;
     float series = d * fmaf(d, fmaf(d, fmaf(d, fmaf(d, fmaf(d, fmaf(d, 1.0f / 7.0f, 1.0f / 6.0f),
                    0.2f), 0.25f), 1.0f / 3.0f), 0.5f), 1.0f);
-    float direct = -logf(u);
+    float direct = -0.693147180559945309f * __builtin_amdgcn_logf(u);
     return d < 0.0625f ? series : direct;
+}
+
+__device__ __forceinline__ float inv_exp_variate(uint32_t word)
+{
+    return __builtin_amdgcn_rcpf(exp_variate(word));
 }
 
 __device__ __forceinline__ u32x4 stream_load(const u32x4* p)

@@ -111,7 +111,7 @@ __device__ __forceinline__ void finish_row(const VocabPassArgs& a, int64_t row,
         philox4x32_10((uint32_t)(col0 >> 2), (uint32_t)grow, (uint32_t)(grow >> 32), 2u,
                       (uint32_t)a.seed, (uint32_t)(a.seed >> 32), w);
 #pragma unroll
-        for (int j = 0; j < 4; ++j) inv_e2[j] = 1.0f / exp_variate(w[j]);   // while the columns arrive
+        for (int j = 0; j < 4; ++j) inv_e2[j] = inv_exp_variate(w[j]);   // while the columns arrive
     }
 
     // Row sums in fp64.
@@ -290,8 +290,8 @@ void vocab_pass_kernel(VocabPassArgs a, int rpb)
             uint32_t w[4];
             philox4x32_10((uint32_t)rem, (uint32_t)grow, (uint32_t)(grow >> 32), 1u, seed_lo, seed_hi, w);
             float4 v;
-            v.x = 1.0f / exp_variate(w[0]); v.y = 1.0f / exp_variate(w[1]);
-            v.z = 1.0f / exp_variate(w[2]); v.w = 1.0f / exp_variate(w[3]);
+            v.x = inv_exp_variate(w[0]); v.y = inv_exp_variate(w[1]);
+            v.z = inv_exp_variate(w[2]); v.w = inv_exp_variate(w[3]);
             reinterpret_cast<float4*>(inv_e_tab)[(size_t)r * nst * 16 + rem] = v;
         }
     }
@@ -462,7 +462,7 @@ void vocab_split_kernel(VocabPassArgs a, RowPartial* __restrict__ ws, int nslots
             philox4x32_10((uint32_t)(tile >> 2), (uint32_t)grow, (uint32_t)(grow >> 32), 1u,
                           (uint32_t)a.seed, (uint32_t)(a.seed >> 32), w);
             const int k = tile & 3;
-            inv_e = 1.0f / exp_variate(k == 0 ? w[0] : k == 1 ? w[1] : k == 2 ? w[2] : w[3]);
+            inv_e = inv_exp_variate(k == 0 ? w[0] : k == 1 ? w[1] : k == 2 ? w[2] : w[3]);
         }
         if (st < nfull) {
             const bool refill = st + 1 < st_end && st + 1 < nfull;     // uniform
