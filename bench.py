@@ -43,7 +43,7 @@ BYTES_PER_ROW = V * 2 + 4 + 12
 # HBM bytes per launch of the sample kernel from rocprofv3 FETCH_SIZE + WRITE_SIZE, each scaled by
 # what the same counter reads for a device copy of known size (profiles/…hbm_traffic.txt).
 # Valid for the kernel as profiled; set to None when the kernel changes until re-measured.
-MEASURED_TRAFFIC_BYTES = 156_520_424
+MEASURED_TRAFFIC_BYTES = 156_486_797
 
 
 class DispatchEvents:
