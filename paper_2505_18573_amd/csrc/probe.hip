@@ -68,7 +68,7 @@ __global__ void zero_sums_kernel(uint32_t* sums, int from)
 
 hipError_t launch_read_probe(const void* buf, int64_t bytes, uint32_t* sums, hipStream_t stream)
 {
-    // about two logit rows (38 runs) per workgroup, as in the vocabulary pass, but never
+    // 38 runs of 16 KiB per workgroup (two bf16 rows of 151,936 columns), but never
     // more workgroups than checksum slots
     const int64_t n16 = bytes / 16;
     const int64_t runs = n16 / kRunVecs;
