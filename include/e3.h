@@ -117,8 +117,9 @@ int e3_sample_entropy(const void* logits, int dtype, int64_t rows, int64_t V, in
  * the time the kernel began to execute and `stop_event` the time it ended (with a
  * workspace and a small batch: begin of the first of the two kernels, end of the second),
  * so hipEventElapsedTime gives the kernel's own duration without the cost of marker
- * packets recorded around it.  The hook is consumed by that one call; calling it again
- * before replaces the events; NULL, NULL clears it.  Always returns E3_OK.
+ * packets recorded around it.  The hook is consumed by the first such call that reaches its
+ * launch (a call rejected by its argument checks, or with rows == 0, leaves it in place);
+ * calling it again before replaces the events; NULL, NULL clears it.  Always returns E3_OK.
  */
 int e3_time_next_launch(void* start_event, void* stop_event);
 
