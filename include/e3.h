@@ -9,7 +9,13 @@
  * default stream) and return without synchronising: outputs are valid once the
  * stream has reached that point.  All argument checks happen on the host before
  * anything is launched; on error nothing is launched and outputs are untouched.
- * Results are bit-reproducible for fixed inputs (no floating-point atomics).
+ * Results are bit-reproducible: the same call (same inputs, shapes and workspace
+ * choice) gives the same bits in every run, since no floating-point atomics are
+ * used and the order in which a row's columns are summed is fixed by the shape of
+ * the launch.  A row that is part of a different batch (another number of rows, or
+ * with / without a workspace) may run in a differently shaped launch: its token is
+ * then the same except on near-ties, its entropy and log-prob the same up to fp32
+ * rounding of the partial sums.
  *
  * Return value: 0 (E3_OK) or a negative e3_status.
  */
@@ -184,9 +190,14 @@ int e3_sample_restricted(const void* logits, int dtype, int64_t rows, int64_t V,
  * row_mask    [rows] uint8 or NULL; rows with mask 0 (padding) are still written
  *             to logp_out/entropy_out but excluded from the batch sum.
  * logp_out    [rows] fp32 or NULL;  entropy_out [rows] fp32 (required).
- * entropy_sum_out    one double (device) or NULL: sum of entropy_out over kept
- *             rows, accumulated in fp64 in a fixed order.
- * entropy_count_out  one int64 (device) or NULL: number of kept rows.
+ * entropy_sum_out    one double or NULL: sum of entropy_out over kept rows,
+ *             accumulated in fp64 in a fixed order.
+ * entropy_count_out  one int64 or NULL: number of kept rows.
+ *             These two are each written once, by one plain store at the end of the
+ *             last kernel, so they may also point into pinned host memory that the
+ *             device can address (hipHostMalloc): the host then reads H_t's two
+ *             numbers after waiting on an event recorded behind this call, without a
+ *             copy in between.
  * Other arguments as for e3_sample_entropy.
  */
 int e3_logprob_entropy(const void* logits, int dtype, int64_t rows, int64_t V, int64_t row_stride,

@@ -115,6 +115,16 @@ def _check(t: Optional[torch.Tensor], dtype, n: int, name: str, device):
         raise ValueError(f"{name} must be a contiguous {dtype} tensor of {n} elements on {device}")
 
 
+def _check_scalar_out(t: Optional[torch.Tensor], dtype, name: str, device):
+    """A one-element output that one thread stores once: device memory, or pinned host
+    memory (which the device addresses through the same pointer)."""
+    if t is not None and t.device.type == "cpu":
+        if not t.is_pinned():
+            raise ValueError(f"{name}: a host tensor must be pinned")
+        device = t.device
+    _check(t, dtype, 1, name, device)
+
+
 def e3_strerror(status: int) -> str:
     return lib().e3_strerror(int(status)).decode()
 
@@ -230,7 +240,8 @@ def e3_logprob_entropy(logits: torch.Tensor, target_ids: Optional[torch.Tensor],
                        entropy_count_out: Optional[torch.Tensor] = None,
                        workspace=None, want_sum: bool = True):
     """Returns (logp fp32 [rows] or None, entropy fp32 [rows], entropy_sum fp64 [1] or None,
-    entropy_count int64 [1] or None); the sum and count stay on the device."""
+    entropy_count int64 [1] or None); the sum and count stay on the device unless pinned host
+    tensors are passed for them."""
     dt, rows, V, stride = _logits_meta(logits)
     dev = logits.device
     if logp_out is None and target_ids is not None:
@@ -246,8 +257,8 @@ def e3_logprob_entropy(logits: torch.Tensor, target_ids: Optional[torch.Tensor],
     _check(tau_rows, torch.float32, rows, "tau_rows", dev)
     _check(logp_out, torch.float32, rows, "logp_out", dev)
     _check(entropy_out, torch.float32, rows, "entropy_out", dev)
-    _check(entropy_sum_out, torch.float64, 1, "entropy_sum_out", dev)
-    _check(entropy_count_out, torch.int64, 1, "entropy_count_out", dev)
+    _check_scalar_out(entropy_sum_out, torch.float64, "entropy_sum_out", dev)
+    _check_scalar_out(entropy_count_out, torch.int64, "entropy_count_out", dev)
     ws, ws_bytes = _workspace(rows, V, workspace, dev)
     rc = lib().e3_logprob_entropy(_ptr(logits), dt, rows, V, stride, _ptr(target_ids),
                                   _ptr(row_mask), _ptr(tau_rows), float(tau_scalar),

@@ -15,9 +15,10 @@
 //     so every load instruction of a wave covers 1 KiB of contiguous memory, and the
 //     8 chunks one lane sees are exactly one sampler tile;
 //   * a workgroup of 8 waves owns a few whole rows; the super-tiles of those rows are
-//     work items that the waves draw from a ticket counter in LDS, so a wave that is
-//     served faster by the memory system simply takes more of them, and a wave keeps
-//     the first sweeps of its next item in flight while it finishes the current one;
+//     work items dealt to the waves round-robin (wave w takes items w, w + 8, ...), so
+//     which columns a wave sums, and in which order, depends on the shape alone and the
+//     results are the same bit for bit in every run; a wave keeps the first sweeps of
+//     its next item in flight while it finishes the current one;
 //   * a wave accumulates the items it gets from one row in registers (fp32 per lane,
 //     one integer-valued log2 reference per wave that moves by exact powers of two)
 //     and hands over one partial per row; the wave that delivers a row's last item
@@ -38,19 +39,14 @@ struct alignas(16) RowPartial {
 };
 static_assert(sizeof(RowPartial) == 32, "layout");
 
-struct QueueHeader {
-    uint32_t ticket;   // dynamic items handed out so far
-    uint32_t pad[3];
-};
-
-// LDS layout: QueueHeader | uint32 done[rpb] (padded to 16 B) | RowPartial parts[rpb][kWaves+1]
+// LDS layout: uint32 done[rpb] (padded to 16 B) | RowPartial parts[rpb][kWaves+1]
 //             | float inv_e[rpb][nst][64]   (rollout side only)
 __host__ __device__ inline size_t lds_done_bytes(int rpb) { return (size_t)((rpb * 4 + 15) / 16 * 16); }
 
 template <int kWaves>
 __host__ __device__ inline size_t lds_bytes(int rpb, int nst, bool sample)
 {
-    return sizeof(QueueHeader) + lds_done_bytes(rpb) + sizeof(RowPartial) * (size_t)rpb * (kWaves + 1)
+    return lds_done_bytes(rpb) + sizeof(RowPartial) * (size_t)rpb * (kWaves + 1)
          + (sample ? (size_t)rpb * nst * kLanes * sizeof(float) : 0);
 }
 
@@ -242,10 +238,9 @@ void vocab_pass_kernel(VocabPassArgs a, int rpb)
     const int n_ragged = nst > nfull ? nrows : 0;
     const int total = n_ragged + nrows * nfull;
 
-    QueueHeader* hdr = reinterpret_cast<QueueHeader*>(smem);
-    uint32_t* done = reinterpret_cast<uint32_t*>(smem + sizeof(QueueHeader));
-    RowPartial* parts = reinterpret_cast<RowPartial*>(smem + sizeof(QueueHeader) + lds_done_bytes(rpb));
-    float* inv_e_tab = reinterpret_cast<float*>(smem + sizeof(QueueHeader) + lds_done_bytes(rpb)
+    uint32_t* done = reinterpret_cast<uint32_t*>(smem);
+    RowPartial* parts = reinterpret_cast<RowPartial*>(smem + lds_done_bytes(rpb));
+    float* inv_e_tab = reinterpret_cast<float*>(smem + lds_done_bytes(rpb)
                                                 + sizeof(RowPartial) * (size_t)rpb * (kWaves + 1));
 
     const int64_t row_bytes = a.row_stride * (int64_t)Chunk::kElemBytes;
@@ -258,8 +253,8 @@ void vocab_pass_kernel(VocabPassArgs a, int rpb)
         else { const int idx = item - n_ragged; r = idx / nfull; st = idx - r * nfull; }
     };
 
-    // The first item of a wave is static; if it is a complete super-tile its first
-    // sweeps are requested before anything else happens.
+    // Wave w takes items w, w + kWaves, ...; if the first is a complete super-tile its
+    // first sweeps are requested before anything else happens.
     int item = wave;
     bool have = item < total;
     Chunk buf[kAhead];
@@ -272,9 +267,8 @@ void vocab_pass_kernel(VocabPassArgs a, int rpb)
         for (int i = 0; i < kAhead; ++i) buf[i].load(rp, b0 + i * kSweepCols);
     }
 
-    // Workgroup prologue: empty queue state, and (rollout side) the level-1 noise of all
+    // Workgroup prologue: empty hand-over slots, and (rollout side) the level-1 noise of all
     // tiles of the workgroup's rows, one Philox block per thread per four tiles.
-    if (threadIdx.x == 0) hdr->ticket = 0;
     for (int i = threadIdx.x; i < rpb; i += kWaves * 64) done[i] = 0;
     for (int i = threadIdx.x; i < rpb * (kWaves + 1); i += kWaves * 64) {
         RowPartial e;
@@ -300,11 +294,6 @@ void vocab_pass_kernel(VocabPassArgs a, int rpb)
     // pipeline for a full memory latency.
     asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
 
-    auto take_ticket = [&]() -> int {
-        uint32_t t = 0;
-        if (lane == 0) t = atomicAdd(&hdr->ticket, 1u);
-        return kWaves + (int)__builtin_amdgcn_readfirstlane(t);
-    };
     // Hand over what this wave holds for local row r (n_items of its items); the wave
     // that brings the row's count to nst finishes the row.
     auto deliver = [&](LaneState& s, int r, int slot, int n_items) {
@@ -333,7 +322,7 @@ void vocab_pass_kernel(VocabPassArgs a, int rpb)
     // Incomplete super-tiles come first in the item order, so a wave meets them before it
     // enters the pipelined loop.
     while (have && item < n_ragged) {
-        const int next = take_ticket();
+        const int next = item + kWaves;
         const int r = item, st = nfull;
         const char* rowp = base + r * row_bytes;
         const float c = row_scale(r);
@@ -366,7 +355,7 @@ void vocab_pass_kernel(VocabPassArgs a, int rpb)
         float c = row_scale(r_cur);
         const char* rowp = base + r_cur * row_bytes;
         while (true) {
-            const int next = take_ticket();
+            const int next = item + kWaves;
             const float inv_e = kSample ? inv_e_tab[((size_t)r_cur * nst + st_cur) * kLanes + lane] : 0.0f;
             const int64_t this_base = (int64_t)st_cur * kSuperCols + lane_col;
 #pragma unroll
@@ -411,6 +400,7 @@ void vocab_pass_kernel(VocabPassArgs a, int rpb)
             }
             r_cur = r_next;
             st_cur = st_next;
+            item = next;
         }
     }
 }
@@ -554,8 +544,8 @@ LaunchEvents take_launch_events()
     return e;
 }
 
-// Rows per workgroup: enough items that the ticket queue can balance the waves (two
-// per wave; one row of 38 super-tiles at V = 151,936), and the noise table must fit LDS
+// Rows per workgroup: at least two items per wave (one row of 38 super-tiles at
+// V = 151,936 gives a wave 4 or 5), and the noise table must fit LDS
 // (0 = does not fit).  Two 8-wave workgroups are resident per compute unit; what exceeds
 // that is handed out by the hardware dispatcher as workgroups finish.
 template <int kWaves>

@@ -203,6 +203,30 @@ def test_config4_reduced_all_rows_with_mask():
     check_logprob(w.logits, w.target_ids, w.row_mask, None, 1.0, "cfg4 reduced + mask")
 
 
+def test_batch_entropy_sum_stored_into_pinned_host_memory():
+    # the two scalars behind H_t (Eq. 4) may land in pinned host memory; after an event
+    # recorded behind the call the host reads what the device-memory variant holds
+    w = wl.training_pass(DEV, rows=700, masked_fraction=0.25)
+    _, ent_d, s_d, n_d = e3.e3_logprob_entropy(w.logits, w.target_ids, w.row_mask, None, 1.0)
+    host = torch.zeros(2, dtype=torch.int64, pin_memory=True)
+    done = torch.cuda.Event()
+    _, ent_h, s_h, n_h = e3.e3_logprob_entropy(w.logits, w.target_ids, w.row_mask, None, 1.0,
+                                               entropy_sum_out=host[0:1].view(torch.float64),
+                                               entropy_count_out=host[1:2])
+    done.record()
+    done.synchronize()
+    assert s_h.device.type == "cpu" and n_h.device.type == "cpu"
+    assert float(host.numpy()[0:1].view("float64")[0]) == s_d.item()
+    assert int(host[1]) == n_d.item() == int(w.row_mask.sum().item())
+    assert torch.equal(ent_h, ent_d)
+    ref = o.logprob_entropy(wl.host_bits(w.logits), w.target_ids.cpu().numpy(),
+                            w.row_mask.cpu().numpy(), None, 1.0, nthreads=NT)
+    assert s_h.item() == pytest.approx(ref.entropy_sum, rel=1e-6)
+    with pytest.raises(ValueError):
+        e3.e3_logprob_entropy(w.logits, None, None, None, 1.0,
+                              entropy_sum_out=torch.zeros(1, dtype=torch.float64))   # pageable
+
+
 # ---------------------------------------------------------------- config 5
 def test_config5_large_decode_full_size():
     w = wl.large_decode(DEV)
@@ -253,6 +277,23 @@ def test_row_base_batching_and_determinism():
     assert torch.equal(torch.cat([lo[0], hi[0]]), a[0])
     c = e3.e3_sample_entropy(lg, None, 0.9, seed=13, row_base=500)
     assert not torch.equal(c[0], a[0])
+
+
+@pytest.mark.parametrize("rows,V", [(16, V_Q), (700, V_Q), (3000, 32_000), (5000, 4104)])
+def test_repeated_runs_are_bit_identical(rows, V):
+    # every output, not only the token: which wave sums which columns is fixed by the shape
+    g = torch.Generator(device=DEV).manual_seed(rows)
+    lg = (torch.randn((rows, V), generator=g, device=DEV) * 3).to(torch.bfloat16)
+    tg = torch.randint(0, V, (rows,), generator=g, device=DEV).to(torch.int32)
+    other = (torch.randn((rows, V), generator=g, device=DEV) * 3).to(torch.bfloat16)
+    first_s = e3.e3_sample_entropy(lg, None, 0.8, seed=5, row_base=0)
+    first_t = e3.e3_logprob_entropy(lg, tg, None, None, 0.8)
+    for rep in range(4):
+        e3.e3_sample_entropy(other, None, 1.1, seed=rep, row_base=0)      # disturb the timing
+        again_s = e3.e3_sample_entropy(lg, None, 0.8, seed=5, row_base=0)
+        again_t = e3.e3_logprob_entropy(lg, tg, None, None, 0.8)
+        assert all(torch.equal(x, y) for x, y in zip(first_s, again_s))
+        assert all(torch.equal(x, y) for x, y in zip(first_t, again_t))
 
 
 def test_targets_out_of_range_empty_batch_and_masks():
