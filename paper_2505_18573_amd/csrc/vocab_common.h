@@ -210,7 +210,14 @@ __device__ __forceinline__ u32x4 stream_load(const u32x4* p)
 }
 
 // ---------------------------------------------------------------------------
-// chunk loaders: 8 consecutive columns of one lane as fp32
+// chunk loaders: 8 consecutive columns (one eighth of a sampler tile) per lane, as fp32.
+//   load / unpack              the lane's own 8 columns starting at `col` (any sweep,
+//                              also an incomplete one);
+//   load_sweep / unpack_sweep  a complete sweep of 512 columns, read so that every load
+//                              instruction of the wave covers 1 KiB of contiguous
+//                              memory: `col` = first column of the sweep + sweep_col(lane);
+//                              after unpack_sweep the lane holds the 8 columns of tile
+//                              lane tile_lane(lane) of that sweep.
 // ---------------------------------------------------------------------------
 struct ChunkBf16 {
     u32x4 v;
@@ -220,6 +227,10 @@ struct ChunkBf16 {
     {
         v = stream_load(reinterpret_cast<const u32x4*>(row + col * 2));
     }
+    static __device__ __forceinline__ int sweep_col(int lane) { return lane * 8; }
+    static __device__ __forceinline__ int tile_lane(int lane) { return lane; }
+    __device__ __forceinline__ void load_sweep(const char* row, int64_t col) { load(row, col); }
+    __device__ __forceinline__ void unpack_sweep(float z[8], int) const { unpack(z); }
     __device__ __forceinline__ void unpack(float z[8]) const
     {
         z[0] = __uint_as_float(v.x << 16); z[1] = __uint_as_float(v.x & 0xFFFF0000u);
@@ -249,6 +260,32 @@ struct ChunkF32 {
         z[2] = __uint_as_float(a.z); z[3] = __uint_as_float(a.w);
         z[4] = __uint_as_float(b.x); z[5] = __uint_as_float(b.y);
         z[6] = __uint_as_float(b.z); z[7] = __uint_as_float(b.w);
+    }
+    // A sweep of fp32 is 2 KiB: the first load takes 16 bytes per lane from its first
+    // KiB, the second from its second KiB.  Lanes 2k and 2k+1 then hold between them
+    // tile lane k (first loads) and tile lane 32+k (second loads); they trade halves,
+    // so the even lane ends up with tile lane k and the odd one with 32+k.  (Reading the
+    // lane's own 32 bytes instead makes every load instruction span 2 KiB half-used.)
+    static __device__ __forceinline__ int sweep_col(int lane) { return lane * 4; }
+    static __device__ __forceinline__ int tile_lane(int lane) { return (lane >> 1) + ((lane & 1) << 5); }
+    __device__ __forceinline__ void load_sweep(const char* row, int64_t col)
+    {
+        const u32x4* p = reinterpret_cast<const u32x4*>(row + col * 4);
+        a = stream_load(p);
+        b = stream_load(p + 64);
+    }
+    __device__ __forceinline__ void unpack_sweep(float z[8], int lane) const
+    {
+        const bool odd = (lane & 1) != 0;
+        const uint32_t keep[4] = {odd ? b.x : a.x, odd ? b.y : a.y, odd ? b.z : a.z, odd ? b.w : a.w};
+        const uint32_t give[4] = {odd ? a.x : b.x, odd ? a.y : b.y, odd ? a.z : b.z, odd ? a.w : b.w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            // quad_perm [1,0,3,2]: every lane reads its neighbour in the pair
+            const uint32_t recv = (uint32_t)__builtin_amdgcn_mov_dpp((int)give[i], 0xB1, 0xF, 0xF, true);
+            z[i] = __uint_as_float(keep[i]);
+            z[4 + i] = __uint_as_float(recv);
+        }
     }
     static __device__ __forceinline__ float load_one(const char* row, int64_t col)
     {

@@ -244,7 +244,9 @@ void vocab_pass_kernel(VocabPassArgs a, int rpb)
                                                 + sizeof(RowPartial) * (size_t)rpb * (kWaves + 1));
 
     const int64_t row_bytes = a.row_stride * (int64_t)Chunk::kElemBytes;
-    const int64_t lane_col = (int64_t)lane * kChunk;
+    const int64_t lane_col = (int64_t)lane * kChunk;            // own columns (incomplete sweeps)
+    const int64_t sweep_lane_col = Chunk::sweep_col(lane);      // complete sweeps: see the loaders
+    const int tlane = Chunk::tile_lane(lane);                   // tile lane held after unpack_sweep
     const char* base = static_cast<const char*>(a.logits) + row0 * row_bytes;
 
     // item -> (local row, super-tile)
@@ -262,9 +264,9 @@ void vocab_pass_kernel(VocabPassArgs a, int rpb)
     if (have && item >= n_ragged) {
         decode(item, r_cur, st_cur);
         const char* rp = base + r_cur * row_bytes;
-        const int64_t b0 = (int64_t)st_cur * kSuperCols + lane_col;
+        const int64_t b0 = (int64_t)st_cur * kSuperCols + sweep_lane_col;
 #pragma unroll
-        for (int i = 0; i < kAhead; ++i) buf[i].load(rp, b0 + i * kSweepCols);
+        for (int i = 0; i < kAhead; ++i) buf[i].load_sweep(rp, b0 + i * kSweepCols);
     }
 
     // Workgroup prologue: empty hand-over slots, and (rollout side) the level-1 noise of all
@@ -338,9 +340,9 @@ void vocab_pass_kernel(VocabPassArgs a, int rpb)
         if (have && item >= n_ragged) {
             decode(item, r_cur, st_cur);
             const char* rp = base + r_cur * row_bytes;
-            const int64_t b0 = (int64_t)st_cur * kSuperCols + lane_col;
+            const int64_t b0 = (int64_t)st_cur * kSuperCols + sweep_lane_col;
 #pragma unroll
-            for (int i = 0; i < kAhead; ++i) buf[i].load(rp, b0 + i * kSweepCols);
+            for (int i = 0; i < kAhead; ++i) buf[i].load_sweep(rp, b0 + i * kSweepCols);
         }
     }
 
@@ -356,13 +358,13 @@ void vocab_pass_kernel(VocabPassArgs a, int rpb)
         const char* rowp = base + r_cur * row_bytes;
         while (true) {
             const int next = item + kWaves;
-            const float inv_e = kSample ? inv_e_tab[((size_t)r_cur * nst + st_cur) * kLanes + lane] : 0.0f;
-            const int64_t this_base = (int64_t)st_cur * kSuperCols + lane_col;
+            const float inv_e = kSample ? inv_e_tab[((size_t)r_cur * nst + st_cur) * kLanes + tlane] : 0.0f;
+            const int64_t this_base = (int64_t)st_cur * kSuperCols + sweep_lane_col;
 #pragma unroll
             for (int i = 0; i < kDepth - kAhead; ++i) {
                 float z[8];
-                buf[i % kAhead].unpack(z);
-                buf[i % kAhead].load(rowp, this_base + (i + kAhead) * kSweepCols);
+                buf[i % kAhead].unpack_sweep(z, lane);
+                buf[i % kAhead].load_sweep(rowp, this_base + (i + kAhead) * kSweepCols);
                 accumulate_chunk(s, z, c, lane);
             }
             const bool more = next < total;
@@ -370,23 +372,23 @@ void vocab_pass_kernel(VocabPassArgs a, int rpb)
             if (more) {
                 decode(next, r_next, st_next);
                 const char* nrowp = base + r_next * row_bytes;
-                const int64_t next_base = (int64_t)st_next * kSuperCols + lane_col;
+                const int64_t next_base = (int64_t)st_next * kSuperCols + sweep_lane_col;
 #pragma unroll
                 for (int i = kDepth - kAhead; i < kDepth; ++i) {
                     float z[8];
-                    buf[i % kAhead].unpack(z);
-                    buf[i % kAhead].load(nrowp, next_base + (i + kAhead - kDepth) * kSweepCols);
+                    buf[i % kAhead].unpack_sweep(z, lane);
+                    buf[i % kAhead].load_sweep(nrowp, next_base + (i + kAhead - kDepth) * kSweepCols);
                     accumulate_chunk(s, z, c, lane);
                 }
             } else {
 #pragma unroll
                 for (int i = kDepth - kAhead; i < kDepth; ++i) {
                     float z[8];
-                    buf[i % kAhead].unpack(z);
+                    buf[i % kAhead].unpack_sweep(z, lane);
                     accumulate_chunk(s, z, c, lane);
                 }
             }
-            close_tile<kSample>(s, st_cur * kLanes + lane, inv_e, true, c, lane);
+            close_tile<kSample>(s, st_cur * kLanes + tlane, inv_e, true, c, lane);
             ++held;
             if (!more || r_next != r_cur) {
                 deliver(s, r_cur, wave, held);
@@ -430,13 +432,15 @@ void vocab_split_kernel(VocabPassArgs a, RowPartial* __restrict__ ws, int nslots
     const int st_end = (slot + 1) * nst / nslots;
 
     const char* rowp = static_cast<const char*>(a.logits) + row * a.row_stride * (int64_t)Chunk::kElemBytes;
-    const int64_t lane_col = (int64_t)lane * kChunk;
+    const int64_t lane_col = (int64_t)lane * kChunk;            // own columns (incomplete sweeps)
+    const int64_t sweep_lane_col = Chunk::sweep_col(lane);      // complete sweeps: see the loaders
+    const int tlane = Chunk::tile_lane(lane);
 
     Chunk buf[kDepth];
     if (st_begin < nfull) {
-        const int64_t b0 = (int64_t)st_begin * kSuperCols + lane_col;
+        const int64_t b0 = (int64_t)st_begin * kSuperCols + sweep_lane_col;
 #pragma unroll
-        for (int i = 0; i < kDepth; ++i) buf[i].load(rowp, b0 + i * kSweepCols);
+        for (int i = 0; i < kDepth; ++i) buf[i].load_sweep(rowp, b0 + i * kSweepCols);
     }
     const float tau = a.tau_rows ? a.tau_rows[row] : a.tau_scalar;
     const float c = kLog2eF / tau;
@@ -445,7 +449,7 @@ void vocab_split_kernel(VocabPassArgs a, RowPartial* __restrict__ ws, int nslots
     LaneState s;
     fresh(s);
     for (int st = st_begin; st < st_end; ++st) {
-        const int tile = st * kLanes + lane;
+        const int tile = st * kLanes + (st < nfull ? tlane : lane);
         float inv_e = 0.0f;
         if (kSample) {
             uint32_t w[4];
@@ -456,12 +460,12 @@ void vocab_split_kernel(VocabPassArgs a, RowPartial* __restrict__ ws, int nslots
         }
         if (st < nfull) {
             const bool refill = st + 1 < st_end && st + 1 < nfull;     // uniform
-            const int64_t nb = (int64_t)(st + 1) * kSuperCols + lane_col;
+            const int64_t nb = (int64_t)(st + 1) * kSuperCols + sweep_lane_col;
 #pragma unroll
             for (int i = 0; i < kDepth; ++i) {
                 float z[8];
-                buf[i].unpack(z);
-                if (refill) buf[i].load(rowp, nb + i * kSweepCols);
+                buf[i].unpack_sweep(z, lane);
+                if (refill) buf[i].load_sweep(rowp, nb + i * kSweepCols);
                 accumulate_chunk(s, z, c, lane);
             }
             close_tile<kSample>(s, tile, inv_e, true, c, lane);
