@@ -86,6 +86,9 @@ def main() -> int:
     ap.add_argument("--restricted", action="store_true",
                     help="also time e3_sample_restricted (top-k 50, top-p 0.95) on the same batches and "
                          "report it in a `restricted_sampling` object; not part of the step")
+    ap.add_argument("--sizes", action="store_true",
+                    help="also time the two vocabulary-pass kernels and the read probe on other batch "
+                         "sizes and on fp32 logits (back-to-back launches, dispatch events)")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run a plain device copy of one logit buffer 10 times (a kernel of "
                          "known traffic: 155.6 MB read + 155.6 MB written) so that a rocprofv3 "
@@ -242,6 +245,10 @@ def main() -> int:
     out["roofline"]["frac_of_read_ceiling"] = achieved / out["read_ceiling"]["GBps"]
     if args.restricted:
         out["restricted_sampling"] = restricted_leg(e3, batches, stream)
+    if args.sizes:
+        del batches[1:]
+        torch.cuda.empty_cache()
+        out["other_sizes"] = sizes_leg(e3, dev, dev_events)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(batches[0], rewards, offsets)
     print(json.dumps(out))
@@ -269,6 +276,50 @@ def read_ceiling_leg(e3, batches, dev_events, reps: int = 50):
                       "16-KiB runs, xor checksum only)",
             "avg_ms": avg, "median_ms": ms[len(ms) // 2], "GBps": nbytes / (avg * 1e-3) / 1e9,
             "frac_of_hbm_peak": nbytes / (avg * 1e-3) / 1e9 / HBM_PEAK_GBPS}
+
+
+def sizes_leg(e3, dev, dev_events, reps: int = 40):
+    """Sample kernel, training-side kernel and read probe on other row counts of the same
+    vocabulary, bf16 and fp32 logits N(0, 3^2), per-row tau U[0.6, 1.4]: back-to-back launches
+    rotating over buffers that together exceed 1 GB, timed by dispatch events."""
+    res = []
+    for dtype, esz, row_list in ((torch.bfloat16, 2, (16, 64, 256, 1024, 2048, 4096, 16384)),
+                                 (torch.float32, 4, (512, 2048, 8192))):
+        for rows in row_list:
+            nbytes = rows * V * esz
+            nbuf = max(2, min(8, int(2.5e9 // nbytes)))
+            bufs = [(torch.randn((rows, V), device=dev) * 3).to(dtype) for _ in range(nbuf)]
+            tau = (0.6 + 0.8 * torch.rand(rows, device=dev)).float()
+            tok = torch.empty(rows, dtype=torch.int32, device=dev)
+            lp = torch.empty(rows, dtype=torch.float32, device=dev)
+            en = torch.empty(rows, dtype=torch.float32, device=dev)
+            tgt = torch.randint(0, V, (rows,), device=dev).to(torch.int32)
+            ws = e3.new_workspace(rows, V, dev)
+            sums = torch.empty(e3.binding.E3_READ_PROBE_SUMS, dtype=torch.int32, device=dev)
+            calls = {
+                "sample": lambda i: e3.e3_sample_entropy(bufs[i % nbuf], tau, 1.0, 1, 0, token_out=tok,
+                                                         logp_out=lp, entropy_out=en, workspace=ws),
+                "logprob": lambda i: e3.e3_logprob_entropy(bufs[i % nbuf], tgt, None, tau, 1.0, logp_out=lp,
+                                                           entropy_out=en, want_sum=False, workspace=ws),
+                "read": lambda i: e3.e3_read_probe(bufs[i % nbuf], sums),
+            }
+            entry = {"rows": rows, "logits_dtype": "bf16" if esz == 2 else "f32"}
+            for name, fn in calls.items():
+                warm = nbuf + 2                      # every buffer once before timing
+                evs = [dev_events.pair() for _ in range(reps)]
+                for i in range(warm + reps):
+                    if i >= warm:
+                        e3.e3_time_next_launch(evs[i - warm][0].value, evs[i - warm][1].value)
+                    fn(i)
+                torch.cuda.synchronize()
+                ms = [dev_events.elapsed_ms(a, b) for a, b in evs]
+                dev_events.destroy(evs)
+                avg = sum(ms) / len(ms)
+                entry[name] = {"avg_us": avg * 1e3, "frac_of_hbm_peak": nbytes / (avg * 1e-3) / 1e9 / HBM_PEAK_GBPS}
+            res.append(entry)
+            del bufs, calls
+            torch.cuda.empty_cache()
+    return res
 
 
 def restricted_leg(e3, batches, stream, reps: int = 50):
