@@ -411,8 +411,8 @@ void vocab_pass_kernel(VocabPassArgs a, int rpb)
 // Small batches.  When the rows are too few to give every compute unit a workgroup
 // of whole rows, a row is cut into `nslots` runs of consecutive super-tiles and
 // every run gets a one-wave workgroup of its own, so that all of the chip's memory
-// channels are busy even for a single row.  A wave requests a whole super-tile (16
-// sweeps) at once, refills each register with the same sweep of its next super-tile
+// channels are busy even for a single row.  A wave requests a whole super-tile (all
+// kDepth sweeps) at once, refills each register with the same sweep of its next super-tile
 // as soon as it has consumed it, draws the level-1 noise of its own tiles while the
 // loads are in flight, and writes one RowPartial to the workspace.  A second launch
 // of one wave per row merges a row's partials exactly as the row-block kernel's
