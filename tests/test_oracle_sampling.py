@@ -123,7 +123,39 @@ def test_determinism_and_row_base():
     assert np.array_equal(t.logp, a.logp) and np.array_equal(t.entropy, a.entropy)
 
 
-def test_exact_ties_go_to_lowest_index_and_are_flagged():
+def _first_noise_collision(stream, seed, row, n):
+    """Two indices i < j < n whose noise words give the same 23-bit uniform (a birthday
+    collision: about n^2 / 2^24 of them are expected)."""
+    seen = {}
+    for idx in range(n):
+        k = o.noise_word(seed, row, stream, idx) >> 9
+        if k in seen:
+            return seen[k], idx
+        seen[k] = idx
+    return None
+
+
+@pytest.mark.parametrize("level", [1, 2])
+def test_exact_ties_go_to_the_lowest_index_and_are_flagged(level):
+    # an exact tie needs equal logits AND equal noise: take two columns whose uniforms
+    # collide, give them the same logit and push every other column far below
+    n, seed, row = 12_000, 5, 77
+    pair = _first_noise_collision(level, seed, row, n)
+    assert pair is not None
+    i, j = pair
+    z = np.full((1, n), -300.0, np.float32)
+    z[0, i] = z[0, j] = 1.25
+    # level 1: every column its own tile (tile noise indexed by the column);
+    # level 2: one tile holding the whole row (column noise decides)
+    partition = (1, 1, 1) if level == 1 else (n, 1, 1)
+    res = o.sample_entropy(z, None, 1.0, seed=seed, row_base=row, partition=partition)
+    assert res.token[0] == i                       # the lower of the two
+    assert res.near_tie[0] == 1
+    top = res.diag[0, 0:2] if level == 1 else res.diag[0, 2:4]
+    assert top[0] == top[1]
+
+
+def test_equal_masses_and_single_column_rows():
     # two tiles, identical mass: decided by the noise, not flagged unless scores are close
     z = np.zeros((1, 4), np.float32)
     res = o.sample_entropy(z, None, 1.0, seed=1, partition=(2, 2, 1))
@@ -146,3 +178,14 @@ def test_near_tie_flag_rule():
     want = close(s1, s2) | close(c1, c2)
     assert np.array_equal(want.astype(np.uint8), res.near_tie)
     assert res.near_tie.mean() < 0.01
+    # the margin itself: among very many tiny rows some have a top-two gap between 1e-7 and
+    # 1e-5 (relative); exactly those and the closer ones are flagged
+    z = rng.normal(0, 2, (600_000, 8)).astype(np.float32)
+    res = o.sample_entropy(z, None, 1.0, seed=4, partition=(4, 1, 1), nthreads=NT)
+    s1, s2, c1, c2 = res.diag.T
+    def rel_gap(x, y):
+        return (x - y) / np.maximum(np.maximum(np.abs(x), np.abs(y)), 1.0)
+    gap = np.minimum(rel_gap(s1, s2), rel_gap(c1, c2))
+    assert np.array_equal((gap <= 1e-5).astype(np.uint8), res.near_tie)
+    assert ((gap > 1e-7) & (gap <= 1e-5)).sum() >= 3
+    assert ((gap > 1e-5) & (gap <= 1e-4)).sum() >= 3          # and just outside: not flagged
