@@ -296,6 +296,56 @@ def test_repeated_runs_are_bit_identical(rows, V):
         assert all(torch.equal(x, y) for x, y in zip(first_t, again_t))
 
 
+def test_exact_ties_go_to_the_lowest_index_at_both_levels():
+    # An exact tie needs equal logits and equal noise.  Level 1: two tiles whose tile uniforms
+    # collide, one live column each; level 2: two columns of one tile whose column uniforms
+    # collide.  The oracle flags such rows (exempt from token parity), so the rule "ties go to
+    # the lowest index" is asserted here directly.
+    from tests import philox_np
+    seed = 21
+    # level 1: tiles of a 12,000-tile row (V = 768,000)
+    ntiles = 12_000
+    row_id = 3
+    k1 = philox_np.noise_words(seed, row_id, 1, np.arange(ntiles)) >> np.uint32(9)
+    order = np.argsort(k1, kind="stable")
+    same = np.flatnonzero(k1[order][1:] == k1[order][:-1])
+    assert same.size > 0
+    t_lo, t_hi = sorted((int(order[same[0]]), int(order[same[0] + 1])))
+    V1 = ntiles * 64
+    def first_col_of_tile(t):                       # tile(i) = (i / 4096) * 64 + (i % 512) / 8
+        return (t // 64) * 4096 + (t % 64) * 8
+    z1 = torch.full((1, V1), -300.0, dtype=torch.bfloat16, device=DEV)
+    z1[0, first_col_of_tile(t_lo) + 3] = 1.25
+    z1[0, first_col_of_tile(t_hi) + 5] = 1.25
+    for ws in (None, False):
+        tok, _, _ = e3.e3_sample_entropy(z1, None, 1.0, seed=seed, row_base=row_id, workspace=ws)
+        assert tok.item() == first_col_of_tile(t_lo) + 3
+    ref = o.sample_entropy(wl.host_bits(z1), None, 1.0, seed, row_id)
+    assert ref.token[0] == first_col_of_tile(t_lo) + 3 and ref.near_tie[0] == 1
+    # level 2: two columns of one tile, V = 4096 (64 tiles of 64 columns); scan row ids
+    cols = np.arange(4096)
+    tile = (cols % 512) // 8
+    found = None
+    for row_id in range(400):
+        k2 = philox_np.noise_words(seed, row_id, 2, cols) >> np.uint32(9)
+        key = tile.astype(np.int64) * (1 << 23) + k2.astype(np.int64)
+        srt = np.argsort(key, kind="stable")
+        dup = np.flatnonzero(key[srt][1:] == key[srt][:-1])
+        if dup.size:
+            found = (row_id, *sorted((int(srt[dup[0]]), int(srt[dup[0] + 1]))))
+            break
+    assert found is not None
+    row_id, c_lo, c_hi = found
+    z2 = torch.full((1, 4096), -300.0, dtype=torch.bfloat16, device=DEV)
+    z2[0, c_lo] = z2[0, c_hi] = 1.25
+    for ws in (None, False):
+        tok, logp, _ = e3.e3_sample_entropy(z2, None, 1.0, seed=seed, row_base=row_id, workspace=ws)
+        assert tok.item() == c_lo
+        assert logp.item() == pytest.approx(math.log(0.5), rel=1e-5)
+    ref = o.sample_entropy(wl.host_bits(z2), None, 1.0, seed, row_id)
+    assert ref.token[0] == c_lo and ref.near_tie[0] == 1
+
+
 def test_targets_out_of_range_empty_batch_and_masks():
     g = torch.Generator(device=DEV).manual_seed(5)
     lg = (torch.randn((6, 1000), generator=g, device=DEV) * 2).float()
