@@ -68,7 +68,11 @@ PINS = {
                    (RES, "test_top_k_one_is_the_argmax_with_logp_zero", {}),
                    (RES, "test_top_p_matches_sort_and_cumsum_on_distinct_values", {}),
                    (RES, "test_hand_worked_dyadic_row", {}),
-                   (RES, "test_all_equal_row_is_uniform_and_minus_zero_ranks_below_plus_zero", {})],
+                   (RES, "test_draw_follows_the_truncated_softmax_with_repeated_values", {}),
+                   (RES, "test_draw_matches_a_numpy_restatement", {"top_k": 12, "top_p": 0.9}),
+                   (RES, "test_draw_matches_a_numpy_restatement", {"top_k": 0, "top_p": 1.0}),
+                   (RES, "test_all_equal_row_is_uniform_and_minus_zero_ranks_below_plus_zero", {}),
+                   (RES, "test_rows_are_keyed_by_global_row_id", {})],
 }
 
 # (name, part whose pins run, text to find (exactly once), replacement)
@@ -101,6 +105,12 @@ MUTANTS = [
      "        double tau = row_tau(tau_rows, tau_scalar, r);\n"
      "        row_stats st = softmax_stats(row, dtype, V, tau);\n"
      "        entropy_out[r]"),
+    ("log-softmax: normaliser added instead of subtracted", "entropy",
+     "out[i] = load_logit(row, dtype, (size_t)i) / tau - st.m - lnS;",
+     "out[i] = load_logit(row, dtype, (size_t)i) / tau - st.m + lnS;"),
+    ("rollout-side log-prob forgets the temperature", "sampling",
+     "logp_out[r] = load_logit(row, dtype, (size_t)tok) / tau - st.m - log(st.S);",
+     "logp_out[r] = load_logit(row, dtype, (size_t)tok) - st.m - log(st.S);"),
     # counter-based generator
     ("Philox: multipliers swapped", "rng",
      "uint64_t pa = M_A * (uint64_t)c0;", "uint64_t pa = M_B * (uint64_t)c0;"),
@@ -144,7 +154,15 @@ MUTANTS = [
     ("advantages: group boundary off by one", "advantages",
      "int64_t lo = group_offsets[g], hi = group_offsets[g + 1];\n        int64_t n = hi - lo;\n        if (n <= 0) continue;\n        double rmax",
      "int64_t lo = group_offsets[g], hi = group_offsets[g + 1] - 1;\n        int64_t n = hi - lo;\n        if (n <= 0) continue;\n        double rmax"),
+    ("advantages: eps not added", "advantages",
+     "adv_out[i] = ((double)rewards[i] - mean) / (sigma + eps);", "adv_out[i] = ((double)rewards[i] - mean) / sigma;"),
     # Eq. 4 / Eq. 5
+    ("Eq. 4: lower clamp missing", "temperature", "if (next < tau_min) next = tau_min;\n    if (next > tau_max) next = tau_max;\n    *tau_next_out = next;\n    if (H_target_out) *H_target_out = target;\n    return 0;\n}\n\nint e3o_max_threads",
+     "if (next > tau_max) next = tau_max;\n    *tau_next_out = next;\n    if (H_target_out) *H_target_out = target;\n    return 0;\n}\n\nint e3o_max_threads"),
+    ("Eq. 4: two-entry vocabulary accepted", "temperature",
+     "!(H_init > 0.0) || !isfinite(H_init) || vocab < 3 ||", "!(H_init > 0.0) || !isfinite(H_init) || vocab < 2 ||"),
+    ("Eq. 5: annealing starts one step late", "temperature",
+     "x = (double)(t - t_anneal) / (double)(t_max - t_anneal);", "x = (double)(t - t_anneal - 1) / (double)(t_max - t_anneal);"),
     ("Eq. 4: ln ln|V| dropped", "temperature",
      "log(alpha) / (lnV + log(lnV))", "log(alpha) / (lnV)"),
     ("Eq. 4: alpha inverted", "temperature", "double alpha = target / H_t;", "double alpha = H_t / target;"),
@@ -168,7 +186,17 @@ MUTANTS = [
      "if (g > G_max) g = G_max;\n        G_out[i] = (int32_t)g;", "G_out[i] = (int32_t)g;"),
     ("bounds: both move up", "budgets",
      "int64_t lo = (int64_t)G - (int64_t)step * passes_done;", "int64_t lo = (int64_t)G + (int64_t)step * passes_done;"),
+    ("Algorithm 1: greedy pass ignores G_max", "budgets",
+     "if (G_out[i] < G_max) { G_out[i] += 1; left -= 1; }", "{ G_out[i] += 1; left -= 1; }"),
+    ("ranks: ties broken by the higher index", "budgets",
+     "if (avg_j > avg_i || (avg_j == avg_i && j < i)) ++ahead;", "if (avg_j > avg_i || (avg_j == avg_i && j > i)) ++ahead;"),
+    ("ranks: unseen questions rank as easiest", "budgets",
+     "double avg_i = cum_rollouts[i] > 0 ? cum_reward[i] / (double)cum_rollouts[i] : 0.0;",
+     "double avg_i = cum_rollouts[i] > 0 ? cum_reward[i] / (double)cum_rollouts[i] : 1e30;"),
     # Appendix A's measured gap
+    ("gap update: alpha inverted", "gap",
+     "double next = tau_t * (1.0 + tau_t * log(target / H_t) / delta);",
+     "double next = tau_t * (1.0 + tau_t * log(H_t / target) / delta);"),
     ("gap: the maximum is not excluded", "gap", "if (i == imax) continue;", ""),
     ("gap: unweighted mean", "gap", "weighted += gap * e;", "weighted += gap; e = 1.0;"),
     ("gap update: Delta multiplies", "gap",
@@ -187,7 +215,19 @@ MUTANTS = [
      "*objective_out = num_groups > 0 ? total / (double)num_groups : 0.0;",
      "{ int nz = 0; for (int32_t q = 0; q < num_groups; ++q) nz += group_offsets[q + 1] > group_offsets[q];\n"
      "      *objective_out = nz > 0 ? total / (double)nz : 0.0; }"),
+    ("objective: group mean replaced by a sum", "objective",
+     "if (i1 > i0) total += group_sum / (double)(i1 - i0);", "if (i1 > i0) total += group_sum;"),
     # restricted sampling
+    ("restricted: race noise indexed by the rank instead of the bit pattern", "restricted",
+     "e3o_noise_word(seed, grow, 3u, it[lv_first[j]].bits)", "e3o_noise_word(seed, grow, 3u, (uint32_t)j)"),
+    ("restricted: race mass forgets the multiplicity", "restricted",
+     "double mass = (double)(LV_END(j) - lv_first[j]) * exp((z - z1) / tau);", "double mass = exp((z - z1) / tau);"),
+    ("restricted: position scaled by the wrong power of two", "restricted",
+     "int64_t pos = (int64_t)(((2u * k23 + 1u) * (uint64_t)n) >> 24);", "int64_t pos = (int64_t)(((2u * k23 + 1u) * (uint64_t)n) >> 25);"),
+    ("restricted: kept count one level short", "restricted",
+     "if (kept_out) kept_out[r] = (int32_t)LV_END(jp);", "if (kept_out) kept_out[r] = (int32_t)lv_first[jp];"),
+    ("restricted: levels ranked lowest first", "restricted",
+     "if (a->ord != b->ord) return a->ord > b->ord ? -1 : 1;", "if (a->ord != b->ord) return a->ord < b->ord ? -1 : 1;"),
     ("top-k: one level too many", "restricted",
      "while (LV_END(jk) < (int64_t)top_k) ++jk;", "while (LV_END(jk) <= (int64_t)top_k) ++jk;"),
     ("top-p: threshold against the whole row instead of the top-k set", "restricted",

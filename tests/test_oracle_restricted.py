@@ -134,6 +134,52 @@ def test_draw_follows_the_truncated_softmax_with_repeated_values():
     assert np.abs(res.logp - np.log(np.where(keep2, p, 1.0))[res.token]).max() < 1e-9
 
 
+def _restate_draw(bits_row, tau, top_k, top_p, seed, row):
+    """The library's definition of the restricted draw written again with numpy and the
+    tests' own Philox: levels by bit pattern, race n_j w_j / E_j with the noise of stream 3
+    indexed by the level's bit pattern, then the pos-th column with stream 4, index 0."""
+    from tests import philox_np
+    vals = (bits_row.astype(np.uint32) << 16).view(np.float32).astype(np.float64)
+    key = np.where(bits_row & 0x8000, 0xFFFF - bits_row.astype(np.int64), bits_row.astype(np.int64) + 0x10000)
+    patterns = sorted(set(bits_row.tolist()), key=lambda b: -int(key[np.flatnonzero(bits_row == b)[0]]))
+    z1 = vals[np.flatnonzero(bits_row == patterns[0])[0]]
+    n = np.array([(bits_row == b).sum() for b in patterns], dtype=np.float64)
+    zl = np.array([vals[np.flatnonzero(bits_row == b)[0]] for b in patterns])
+    w = np.exp((zl - z1) / tau)
+    C, M = np.cumsum(n), np.cumsum(n * w)
+    jk = len(patterns) - 1
+    if 1 <= top_k < bits_row.size:
+        jk = int(np.flatnonzero(C >= top_k)[0])
+    jp = jk
+    if top_p < 1.0:
+        jp = int(np.flatnonzero(M[:jk + 1] >= top_p * M[jk])[0])
+    words = philox_np.noise_words(seed, row, 3, np.array(patterns[:jp + 1], dtype=np.uint64))
+    E = -np.log(((words >> np.uint32(9)).astype(np.float64) + 0.5) / 8388608.0)
+    best = int(np.argmax(n[:jp + 1] * w[:jp + 1] / E))
+    k23 = int(philox_np.noise_words(seed, row, 4, np.array([0]))[0]) >> 9
+    pos = ((2 * k23 + 1) * int(n[best])) >> 24
+    cols = np.flatnonzero(bits_row == patterns[best])
+    return int(cols[pos]), int(C[jp]), (zl[best] - z1) / tau - math.log(M[jp])
+
+
+@pytest.mark.parametrize("top_k,top_p", [(0, 1.0), (9, 1.0), (0, 0.8), (12, 0.9), (1, 0.5)])
+def test_draw_matches_a_numpy_restatement(top_k, top_p):
+    # few distinct values (many repeats), both signs, 300 rows with their own noise
+    rng = np.random.default_rng(17)
+    grid = np.array([-2.0, -1.0, -0.5, -0.0, 0.0, 0.25, 0.5, 1.0, 1.5, 2.0, 3.0], dtype=np.float32)
+    rows, V, seed, base = 300, 40, 23, 1000
+    z = bf16_bits(rng.choice(grid, size=(rows, V)))
+    tau = np.float32(0.8)
+    res = o.sample_restricted(z, None, float(tau), top_k, top_p, seed=seed, row_base=base, nthreads=4)
+    for r in range(rows):
+        if res.near_tie[r] or res.near_cut[r]:
+            continue
+        tok, kept, logp = _restate_draw(z[r], float(tau), top_k, float(np.float32(top_p)), seed, base + r)
+        assert (res.token[r], res.kept[r]) == (tok, kept), r
+        assert res.logp[r] == pytest.approx(logp, abs=1e-12)
+    assert (res.near_tie | res.near_cut).mean() < 0.2
+
+
 def test_all_equal_row_is_uniform_and_minus_zero_ranks_below_plus_zero():
     z = bf16_bits(np.full((1, 16), 0.25, dtype=np.float32))
     n = 32_000
