@@ -544,3 +544,67 @@ def test_batch_between_resident_rounds_uses_small_workgroups():
     check_sample(lg, tau, 1.0, seed=12, row_base=5, label="600 x 65544")
     tgt = torch.randint(0, lg.shape[1], (600,), generator=g, device=DEV).to(torch.int32)
     check_logprob(lg, tgt, None, tau, 1.0, "600 x 65544 logprob")
+
+
+# ---------------------------------------------------------------- are the checks sharp?
+@pytest.fixture()
+def wrong_oracle(tmp_path):
+    """Puts a copy of the oracle with one planted mistake behind its front end (the mistake
+    is always planted on the CPU side; the library is untouched)."""
+    from tests import test_oracle_mutants as mut
+    real = o.lib()
+    source = open(mut.SRC).read()
+
+    def plant(find, replace):
+        assert source.count(find) == 1
+        o._lib = mut._build(tmp_path, "wrong", source.replace(find, replace))
+    yield plant
+    o._lib = real
+
+
+def _parity_batch():
+    g = torch.Generator(device=DEV).manual_seed(77)
+    lg = (torch.randn((24, 20_000), generator=g, device=DEV) * 3).to(torch.bfloat16)
+    tau = (0.6 + 0.8 * torch.rand(24, generator=g, device=DEV)).float()
+    tgt = torch.randint(0, 20_000, (24,), generator=g, device=DEV).to(torch.int32)
+    return lg, tau, tgt
+
+
+@pytest.mark.parametrize("what,find,replace", [
+    ("entropy 3e-4 too large", "return log(st.S) - st.W / st.S;", "return (log(st.S) - st.W / st.S) * 1.0003;"),
+    ("log-prob 3e-4 off", "? load_logit(row, dtype, (size_t)t) / tau - st.m - log(st.S) : NAN;",
+     "? (load_logit(row, dtype, (size_t)t) / tau - st.m - log(st.S)) * 1.0003 : NAN;"),
+    ("batch sum counts masked rows", "if (!row_mask || row_mask[r]) { sum += entropy_out[r]; ++cnt; }",
+     "{ sum += entropy_out[r]; ++cnt; }"),
+], ids=["entropy", "logp", "masked-sum"])
+def test_training_side_parity_check_notices_a_wrong_oracle(what, find, replace, wrong_oracle):
+    lg, tau, tgt = _parity_batch()
+    mask = (torch.arange(24, device=DEV) % 3 != 0).to(torch.uint8)
+    check_logprob(lg, tgt, mask, tau, 1.0, "control")                   # the real oracle agrees
+    wrong_oracle(find, replace)
+    with pytest.raises(AssertionError):
+        check_logprob(lg, tgt, mask, tau, 1.0, what)
+
+
+@pytest.mark.parametrize("what,find,replace", [
+    ("column noise from the tile stream", "e3o_noise_word(seed, grow, 2u, (uint32_t)i)",
+     "e3o_noise_word(seed, grow, 1u, (uint32_t)i)"),
+    ("tile noise keyed by the local row", "int32_t tok = sample_row(row, dtype, V, tau, st, seed, row_base + (uint64_t)r,",
+     "int32_t tok = sample_row(row, dtype, V, tau, st, seed, (uint64_t)r,"),
+    ("rollout-side log-prob 3e-4 off", "logp_out[r] = load_logit(row, dtype, (size_t)tok) / tau - st.m - log(st.S);",
+     "logp_out[r] = (load_logit(row, dtype, (size_t)tok) / tau - st.m - log(st.S)) * 1.0003;"),
+], ids=["column-stream", "local-row", "logp"])
+def test_rollout_side_parity_check_notices_a_wrong_oracle(what, find, replace, wrong_oracle):
+    lg, tau, _ = _parity_batch()
+    check_sample(lg, tau, 1.0, seed=5, row_base=1000, label="control")
+    wrong_oracle(find, replace)
+    with pytest.raises(AssertionError):
+        check_sample(lg, tau, 1.0, seed=5, row_base=1000, label=what)
+
+
+def test_parity_checks_accept_an_oracle_off_by_a_rounding_error(wrong_oracle):
+    # 1e-6 relative is inside the 1e-4 tolerance: the checks must not be tighter than stated
+    lg, tau, tgt = _parity_batch()
+    wrong_oracle("return log(st.S) - st.W / st.S;", "return (log(st.S) - st.W / st.S) * 1.000001;")
+    check_logprob(lg, tgt, None, tau, 1.0, "entropy 1e-6 off")
+    check_sample(lg, tau, 1.0, seed=5, row_base=1000, label="entropy 1e-6 off")
