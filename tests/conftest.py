@@ -20,3 +20,20 @@ def pytest_collection_modifyitems(config, items):
     for item in items:
         if "gpu" in item.keywords:
             item.add_marker(skip)
+
+
+@pytest.fixture()
+def wrong_oracle(tmp_path):
+    """plant(find, replace): puts a copy of the oracle with one planted mistake behind its
+    Python front end until the test ends.  The mistake is always planted on the CPU side,
+    in the oracle; the HIP library is untouched."""
+    from oracle import e3_oracle as o
+    from tests import test_oracle_mutants as mut
+    real = o.lib()
+    source = open(mut.SRC).read()
+
+    def plant(find, replace):
+        assert source.count(find) == 1
+        o._lib = mut._build(tmp_path, "wrong", source.replace(find, replace))
+    yield plant
+    o._lib = real

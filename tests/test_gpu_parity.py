@@ -547,21 +547,6 @@ def test_batch_between_resident_rounds_uses_small_workgroups():
 
 
 # ---------------------------------------------------------------- are the checks sharp?
-@pytest.fixture()
-def wrong_oracle(tmp_path):
-    """Puts a copy of the oracle with one planted mistake behind its front end (the mistake
-    is always planted on the CPU side; the library is untouched)."""
-    from tests import test_oracle_mutants as mut
-    real = o.lib()
-    source = open(mut.SRC).read()
-
-    def plant(find, replace):
-        assert source.count(find) == 1
-        o._lib = mut._build(tmp_path, "wrong", source.replace(find, replace))
-    yield plant
-    o._lib = real
-
-
 def _parity_batch():
     g = torch.Generator(device=DEV).manual_seed(77)
     lg = (torch.randn((24, 20_000), generator=g, device=DEV) * 3).to(torch.bfloat16)

@@ -91,6 +91,25 @@ def test_repeated_values_and_signed_zeros():
 
 
 @pytest.mark.gpu
+def test_top_k_exactly_on_a_level_boundary():
+    # every row is a permutation of one multiset, so the cumulative level counts are the same
+    # in all rows and k can be put exactly on a boundary, one before and one after it
+    counts = [(3.0, 1), (2.5, 37), (1.0, 1200), (0.0, 700), (-0.0, 11), (-1.0, 2500), (-4.0, 551)]
+    base = torch.cat([torch.full((n,), v) for v, n in counts])
+    V = base.numel()
+    g = torch.Generator().manual_seed(3)
+    lg = torch.stack([base[torch.randperm(V, generator=g)] for _ in range(6)]).to(torch.bfloat16).to(DEV)
+    cum = np.cumsum([n for _, n in counts])
+    for j in (0, 1, 2, 3, 4, 5):
+        for k in (int(cum[j]) - 1, int(cum[j]), int(cum[j]) + 1):
+            if k < 1:
+                continue
+            r = check(lg, None, 0.9, k, 1.0, 5, 40, f"boundary level {j} k={k}")
+            want = int(cum[np.searchsorted(cum, k)])          # first cumulative count >= k
+            assert (r.kept == want).all(), (j, k, r.kept, want)
+
+
+@pytest.mark.gpu
 def test_frequencies_follow_the_truncated_softmax():
     vals = torch.tensor([[2.0, 1.5, 2.0, 0.5, 1.5, 1.5, -1.0, 0.5, 0.0, -0.0, 3.0, -2.0, -2.0, 1.0, 0.25, -3.0]],
                         device=DEV)
