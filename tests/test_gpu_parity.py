@@ -446,6 +446,18 @@ def test_wide_rows_more_super_tiles_than_lanes():
     check_logprob(lg, tgt, None, None, 0.8, "141 super-tiles logprob")
 
 
+@pytest.mark.parametrize("dtype", [torch.bfloat16, torch.float32])
+def test_widest_accepted_row(dtype):
+    # 254 complete super-tiles: the level-1 noise table of one row fills the 64 KiB of LDS
+    # a workgroup may ask for; one column more is refused (tests/test_abi.py)
+    V = 1_040_384
+    g = torch.Generator(device=DEV).manual_seed(33)
+    lg = (torch.randn((2, V), generator=g, device=DEV) * 3).to(dtype)
+    check_sample(lg, None, 1.1, seed=6, row_base=9, label=f"widest row {dtype}")
+    tgt = torch.tensor([V - 1, 4096 * 253], dtype=torch.int32, device=DEV)
+    check_logprob(lg, tgt, None, None, 1.1, f"widest row {dtype} logprob")
+
+
 def test_unusable_workspace_falls_back_to_whole_rows():
     g = torch.Generator(device=DEV).manual_seed(22)
     lg = (torch.randn((5, 30_000), generator=g, device=DEV) * 3).to(torch.bfloat16)
