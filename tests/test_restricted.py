@@ -77,6 +77,18 @@ def test_shapes_and_tails(V):
 
 
 @pytest.mark.gpu
+def test_widest_accepted_row():
+    V = 1_040_384
+    g = torch.Generator(device=DEV).manual_seed(44)
+    lg = (torch.randn((2, V), generator=g, device=DEV) * 2.5).to(torch.bfloat16)
+    check(lg, None, 0.9, 50, 0.95, 8, 1, "widest row k=50 p=0.95")
+    check(lg, None, 0.9, 0, 0.9, 8, 1, "widest row p=0.9")
+    same = torch.full((1, V), -1.5, device=DEV).to(torch.bfloat16)     # one level of 1,040,384 columns
+    r = check(same, None, 1.0, 3, 0.5, 2, 0, "widest row, all equal")
+    assert (r.kept == V).all()
+
+
+@pytest.mark.gpu
 def test_repeated_values_and_signed_zeros():
     # few distinct values: every level holds many columns, cuts fall inside repeated values
     g = torch.Generator(device=DEV).manual_seed(8)
