@@ -4,9 +4,10 @@
 One step = one pass of the whole path over one decode batch of the paper's shape
 (Section 5.1: 64 prompts x 8 rollouts; a 151,936-entry vocabulary, bf16 logits):
 
-  1. e3_grpo_advantages  Eq. 2 over the 64 groups of 8 rewards
-  2. e3_logprob_entropy  training side: log-prob of the previously sampled tokens,
-                         entropy, batch entropy sum/count, on the training-pass logits
+  1. + 2. e3_logprob_entropy_advantages  training side, one call: Eq. 2 over the 64 groups of
+                         8 rewards (computed inside the vocabulary pass's launch), log-prob of
+                         the previously sampled tokens, entropy, batch entropy sum/count on
+                         the training-pass logits
   3. e3_sample_entropy   rollout side: token, log-prob, entropy per row      (dominant)
   4. e3_temperature_update (Eq. 4 / Eq. 5) on the host, from the 16 bytes that 2. stores into
      pinned host memory (the host waits for an event behind 2. only, so 4. overlaps 3.)
@@ -43,7 +44,7 @@ BYTES_PER_ROW = V * 2 + 4 + 12
 # HBM bytes per launch of the sample kernel from rocprofv3 FETCH_SIZE + WRITE_SIZE, each scaled by
 # what the same counter reads for a device copy of known size (profiles/…hbm_traffic.txt).
 # Valid for the kernel as profiled; set to None when the kernel changes until re-measured.
-MEASURED_TRAFFIC_BYTES = 156_499_341
+MEASURED_TRAFFIC_BYTES = 156_496_152
 
 
 class DispatchEvents:
@@ -152,10 +153,10 @@ def main() -> int:
         attaches to the sampling kernel's dispatch (begin and end of its execution)."""
         roll = batches[i % nb]
         train = batches[(i + nb // 2) % nb]
-        e3.e3_grpo_advantages(rewards, offsets, 0, 0.0, adv_out=adv)
-        e3.e3_logprob_entropy(train.logits, tok, None, train.tau_rows, 1.0, logp_out=logp_t,
-                              entropy_out=ent_t, entropy_sum_out=hsum, entropy_count_out=hcnt,
-                              workspace=ws)
+        e3.e3_logprob_entropy_advantages(train.logits, tok, None, train.tau_rows, 1.0, rewards, offsets,
+                                         0, 0.0, logp_out=logp_t, entropy_out=ent_t,
+                                         entropy_sum_out=hsum, entropy_count_out=hcnt, adv_out=adv,
+                                         workspace=ws)
         stats_ready.record(stream)
         if ev is not None:
             e3.e3_time_next_launch(ev[0].value, ev[1].value)

@@ -249,6 +249,25 @@ int e3_grpo_advantages(const float* rewards, const int32_t* group_offsets,
                        float* adv_out, void* hip_stream);
 
 /*
+ * e3_logprob_entropy and e3_grpo_advantages in one call: the two sets of statistics a
+ * GRPO update needs of a batch of finished rollouts (Eq. 2's advantages from the
+ * rewards; log-probabilities and entropies from the logits, Section 4.2).  Results are
+ * bit for bit those of the two separate calls.  When the batch runs as whole rows per
+ * workgroup and there are at most as many groups as workgroups, the groups are computed
+ * inside the vocabulary pass's launch by waves that have time to spare, which saves a
+ * launch; otherwise they get a launch of their own first.  Arguments as for the two
+ * calls; num_groups == 0 makes it e3_logprob_entropy.
+ */
+int e3_logprob_entropy_advantages(const void* logits, int dtype, int64_t rows, int64_t V,
+                                  int64_t row_stride, const int32_t* target_ids,
+                                  const uint8_t* row_mask, const float* tau_rows, float tau_scalar,
+                                  float* logp_out, float* entropy_out,
+                                  double* entropy_sum_out, int64_t* entropy_count_out,
+                                  const float* rewards, const int32_t* group_offsets,
+                                  int32_t num_groups, int32_t ddof, float eps, float* adv_out,
+                                  void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
  * Forward value of the GRPO objective, Eq. 1 without the KL term (which the paper
  * drops, Section 3.1):
  *   J = mean_q (1/G_q) sum_{i in q} (1/|o_i|) sum_t min( r A_i , clip(r, 1-eps, 1+eps) A_i ),

@@ -21,7 +21,7 @@ E3_OK = 0
 E3_TILE_CHUNK, E3_TILE_LANES, E3_TILE_DEPTH = 8, 64, 8
 
 EXPORTS = ("e3_strerror", "e3_workspace_bytes", "e3_sample_entropy", "e3_sample_restricted",
-           "e3_logprob_entropy",
+           "e3_logprob_entropy", "e3_logprob_entropy_advantages",
            "e3_grpo_advantages", "e3_temperature_update", "e3_difficulty_ranks",
            "e3_allocate_budgets", "e3_budget_bounds", "e3_logprob_entropy_gap",
            "e3_temperature_update_gap", "e3_grpo_objective", "e3_read_probe",
@@ -62,6 +62,10 @@ def lib() -> C.CDLL:
         L.e3_logprob_entropy.argtypes = [vp, C.c_int, i64, i64, i64, vp, vp, vp, f32,
                                          vp, vp, vp, vp, vp, C.c_size_t, vp]
         L.e3_logprob_entropy.restype = C.c_int
+        L.e3_logprob_entropy_advantages.argtypes = [vp, C.c_int, i64, i64, i64, vp, vp, vp, f32,
+                                                    vp, vp, vp, vp, vp, vp, i32, i32, f32, vp,
+                                                    vp, C.c_size_t, vp]
+        L.e3_logprob_entropy_advantages.restype = C.c_int
         L.e3_logprob_entropy_gap.argtypes = [vp, C.c_int, i64, i64, i64, vp, vp, vp, f32,
                                              vp, vp, vp, vp, vp, vp, vp, C.c_size_t, vp]
         L.e3_logprob_entropy_gap.restype = C.c_int
@@ -268,6 +272,54 @@ def e3_logprob_entropy(logits: torch.Tensor, target_ids: Optional[torch.Tensor],
     if rc != E3_OK:
         raise E3Error(rc, "e3_logprob_entropy")
     return logp_out, entropy_out, entropy_sum_out, entropy_count_out
+
+
+def e3_logprob_entropy_advantages(logits: torch.Tensor, target_ids: Optional[torch.Tensor],
+                                  row_mask: Optional[torch.Tensor], tau_rows: Optional[torch.Tensor],
+                                  tau_scalar: float, rewards: torch.Tensor, group_offsets: torch.Tensor,
+                                  ddof: int = 0, eps: float = 0.0,
+                                  logp_out: Optional[torch.Tensor] = None,
+                                  entropy_out: Optional[torch.Tensor] = None,
+                                  entropy_sum_out: Optional[torch.Tensor] = None,
+                                  entropy_count_out: Optional[torch.Tensor] = None,
+                                  adv_out: Optional[torch.Tensor] = None,
+                                  workspace=None, want_sum: bool = True):
+    """e3_logprob_entropy and e3_grpo_advantages in one call.  Returns (logp, entropy,
+    entropy_sum, entropy_count, adv)."""
+    dt, rows, V, stride = _logits_meta(logits)
+    dev = logits.device
+    n = rewards.shape[0]
+    num_groups = group_offsets.shape[0] - 1
+    if logp_out is None and target_ids is not None:
+        logp_out = torch.empty(rows, dtype=torch.float32, device=dev)
+    if entropy_out is None:
+        entropy_out = torch.empty(rows, dtype=torch.float32, device=dev)
+    if want_sum and entropy_sum_out is None:
+        entropy_sum_out = torch.empty(1, dtype=torch.float64, device=dev)
+    if want_sum and entropy_count_out is None:
+        entropy_count_out = torch.empty(1, dtype=torch.int64, device=dev)
+    if adv_out is None:
+        adv_out = torch.empty(n, dtype=torch.float32, device=dev)
+    _check(target_ids, torch.int32, rows, "target_ids", dev)
+    _check(row_mask, torch.uint8, rows, "row_mask", dev)
+    _check(tau_rows, torch.float32, rows, "tau_rows", dev)
+    _check(logp_out, torch.float32, rows, "logp_out", dev)
+    _check(entropy_out, torch.float32, rows, "entropy_out", dev)
+    _check_scalar_out(entropy_sum_out, torch.float64, "entropy_sum_out", dev)
+    _check_scalar_out(entropy_count_out, torch.int64, "entropy_count_out", dev)
+    _check(rewards, torch.float32, n, "rewards", dev)
+    _check(group_offsets, torch.int32, num_groups + 1, "group_offsets", dev)
+    _check(adv_out, torch.float32, n, "adv_out", dev)
+    ws, ws_bytes = _workspace(rows, V, workspace, dev)
+    rc = lib().e3_logprob_entropy_advantages(_ptr(logits), dt, rows, V, stride, _ptr(target_ids),
+                                             _ptr(row_mask), _ptr(tau_rows), float(tau_scalar),
+                                             _ptr(logp_out), _ptr(entropy_out),
+                                             _ptr(entropy_sum_out), _ptr(entropy_count_out),
+                                             _ptr(rewards), _ptr(group_offsets), num_groups, int(ddof),
+                                             float(eps), _ptr(adv_out), _ptr(ws), ws_bytes, _stream(dev))
+    if rc != E3_OK:
+        raise E3Error(rc, "e3_logprob_entropy_advantages")
+    return logp_out, entropy_out, entropy_sum_out, entropy_count_out, adv_out
 
 
 def e3_grpo_advantages(rewards: torch.Tensor, group_offsets: torch.Tensor, ddof: int = 0,

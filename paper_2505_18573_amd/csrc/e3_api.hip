@@ -150,6 +150,45 @@ extern "C" int e3_logprob_entropy_gap(const void* logits, int dtype, int64_t row
     return E3_OK;
 }
 
+extern "C" int e3_logprob_entropy_advantages(const void* logits, int dtype, int64_t rows, int64_t V,
+                                            int64_t row_stride, const int32_t* target_ids,
+                                            const uint8_t* row_mask, const float* tau_rows,
+                                            float tau_scalar, float* logp_out, float* entropy_out,
+                                            double* entropy_sum_out, int64_t* entropy_count_out,
+                                            const float* rewards, const int32_t* group_offsets,
+                                            int32_t num_groups, int32_t ddof, float eps, float* adv_out,
+                                            void* workspace, size_t workspace_bytes, void* hip_stream)
+{
+    int rc = check_logits(logits, dtype, rows, V, row_stride);
+    if (rc != E3_OK) return rc;
+    rc = check_tau(tau_rows, tau_scalar);
+    if (rc != E3_OK) return rc;
+    if (rows > 0 && entropy_out == nullptr) return E3_ERR_NULL;
+    if (logp_out != nullptr && target_ids == nullptr) return E3_ERR_NULL;
+    if (num_groups < 0) return E3_ERR_SHAPE;
+    if (ddof != 0 && ddof != 1) return E3_ERR_VALUE;
+    if (!(eps >= 0.0f) || !std::isfinite(eps)) return E3_ERR_VALUE;
+    if (num_groups > 0 && (rewards == nullptr || group_offsets == nullptr || adv_out == nullptr))
+        return E3_ERR_NULL;
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+
+    e3::VocabPassArgs a{};
+    a.logits = logits; a.rows = rows; a.V = V; a.row_stride = row_stride;
+    a.tau_rows = tau_rows; a.tau_scalar = tau_scalar;
+    a.target_ids = target_ids;
+    a.token_out = nullptr; a.logp_out = logp_out; a.entropy_out = entropy_out;
+    a.adv_rewards = rewards; a.adv_offsets = group_offsets; a.adv_groups = num_groups;
+    a.adv_ddof = ddof; a.adv_eps = eps; a.adv_out = adv_out;
+    if (e3::launch_vocab_pass(a, dtype == E3_BF16, false, workspace, workspace_bytes, stream) != hipSuccess)
+        return E3_ERR_LAUNCH;
+    if (entropy_sum_out != nullptr || entropy_count_out != nullptr) {
+        if (e3::launch_entropy_reduce(entropy_out, row_mask, rows, entropy_sum_out, entropy_count_out,
+                                      stream) != hipSuccess)
+            return E3_ERR_LAUNCH;
+    }
+    return E3_OK;
+}
+
 extern "C" int e3_logprob_entropy(const void* logits, int dtype, int64_t rows, int64_t V,
                                   int64_t row_stride, const int32_t* target_ids,
                                   const uint8_t* row_mask, const float* tau_rows, float tau_scalar,

@@ -16,6 +16,13 @@ struct VocabPassArgs {
     float* logp_out;                  // nullable
     float* entropy_out;               // nullable
     float* gap_out;                   // nullable: measured logit gap (Appendix A's Delta)
+    // training side, optional: rollout groups whose advantages (Eq. 2) are computed in the
+    // same launch (adv_groups == 0: none)
+    const float* adv_rewards;
+    const int32_t* adv_offsets;
+    int32_t adv_groups, adv_ddof;
+    float adv_eps;
+    float* adv_out;
 };
 
 // `workspace` (device, 16-byte aligned, nullable) lets small batches be cut across

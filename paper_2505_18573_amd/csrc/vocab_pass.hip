@@ -24,6 +24,7 @@
 //     and hands over one partial per row; the wave that delivers a row's last item
 //     merges the partials in fp64, runs level 2 of the sampler and writes the outputs
 //     while the other waves keep streaming.
+#include "advantages.h"
 #include "vocab_common.h"
 #include "vocab_pass.h"
 #include <hip/hip_ext.h>
@@ -295,6 +296,14 @@ void vocab_pass_kernel(VocabPassArgs a, int rpb)
     // global loads already in flight (its fence covers global memory) and drain the
     // pipeline for a full memory latency.
     asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+
+    // Training side, optional: rollout groups riding along.  The last wave has the fewest
+    // items (or as many as the others), so it takes workgroup b's group b before it starts
+    // on its own; the loads of its first item are already in flight.  The host asks for
+    // this only when there are at most as many groups as workgroups.
+    if (!kSample && a.adv_groups > 0 && wave == kWaves - 1 && (int)blockIdx.x < a.adv_groups)
+        advantages_of_group(a.adv_rewards, a.adv_offsets, (int)blockIdx.x, a.adv_ddof, a.adv_eps,
+                            a.adv_out, lane);
 
     // Hand over what this wave holds for local row r (n_items of its items); the wave
     // that brings the row's count to nst finishes the row.
@@ -675,9 +684,28 @@ static hipError_t launch_split(const VocabPassArgs& a, RowPartial* ws, SplitPlan
     return hipGetLastError();
 }
 
-hipError_t launch_vocab_pass(const VocabPassArgs& a, bool is_bf16, bool sample,
+// Number of workgroups the row-block launch of this shape will have (both wave counts
+// give the same number when a workgroup holds one row).
+template <int kWaves>
+static int64_t row_block_groups(int64_t rows, int64_t V, bool sample)
+{
+    const int rpb = rows_per_group<kWaves>(V, sample);
+    return rpb > 0 ? (rows + rpb - 1) / rpb : 0;
+}
+
+hipError_t launch_vocab_pass(const VocabPassArgs& args, bool is_bf16, bool sample,
                              void* workspace, size_t workspace_bytes, hipStream_t stream)
 {
+    VocabPassArgs a = args;
+    // Groups ride along only in a row-block launch that has a workgroup for each of them
+    // with either wave count; otherwise they get their own launch first.
+    auto separate_advantages = [&]() -> hipError_t {
+        const hipError_t err = launch_grpo_advantages(a.adv_rewards, a.adv_offsets, a.adv_groups,
+                                                      a.adv_ddof, a.adv_eps, a.adv_out, stream);
+        a.adv_groups = 0;
+        return err;
+    };
+    if (a.adv_groups > 0 && a.rows == 0) return separate_advantages();
     if (a.rows == 0) return hipSuccess;
     const int cus = compute_units();
     const int rpb8 = rows_per_group<8>(a.V, sample);
@@ -691,11 +719,22 @@ hipError_t launch_vocab_pass(const VocabPassArgs& a, bool is_bf16, bool sample,
         const SplitPlan plan = split_plan(a.V);
         if ((size_t)a.rows * plan.nslots * sizeof(RowPartial) <= workspace_bytes) {
             RowPartial* ws = static_cast<RowPartial*>(workspace);
+            if (a.adv_groups > 0) {
+                const hipError_t err = separate_advantages();
+                if (err != hipSuccess) return err;
+            }
             if (is_bf16)
                 return sample ? launch_split<ChunkBf16, true>(a, ws, plan, stream)
                               : launch_split<ChunkBf16, false>(a, ws, plan, stream);
             return sample ? launch_split<ChunkF32, true>(a, ws, plan, stream)
                           : launch_split<ChunkF32, false>(a, ws, plan, stream);
+        }
+    }
+    if (a.adv_groups > 0) {
+        const int64_t g8 = row_block_groups<8>(a.rows, a.V, sample), g4 = row_block_groups<4>(a.rows, a.V, sample);
+        if (sample || a.adv_groups > g8 || a.adv_groups > g4) {
+            const hipError_t err = separate_advantages();
+            if (err != hipSuccess) return err;
         }
     }
     if (is_bf16)

@@ -90,6 +90,14 @@ def test_logprob_entropy_argument_checks():
 def test_grpo_argument_checks():
     L = e3.lib()
     assert L.e3_grpo_advantages(0x1000, 0x2000, -1, 0, 0.0, 0x3000, None) == -2
+    # the combined call checks both halves before anything is launched
+    def both(rows=4, V=64, ent=0x4000, groups=2, ddof=0, eps=0.0, rew=0x5000, off=0x6000, adv=0x7000):
+        return L.e3_logprob_entropy_advantages(0x1000, 1, rows, V, 64, None, None, None, 1.0, None, ent,
+                                               None, None, rew, off, groups, ddof, eps, adv, None, 0, None)
+    assert both(ent=None) == -1 and both(groups=-1) == -2 and both(ddof=2) == -5
+    assert both(eps=-1.0) == -5 and both(adv=None) == -1 and both(rew=None) == -1
+    assert both(V=0) == -2
+    assert both(rows=0, groups=0, rew=None, off=None, adv=None, ent=None) == 0
     assert L.e3_grpo_advantages(0x1000, 0x2000, 4, 2, 0.0, 0x3000, None) == -5
     assert L.e3_grpo_advantages(0x1000, 0x2000, 4, 0, -1.0, 0x3000, None) == -5
     assert L.e3_grpo_advantages(None, 0x2000, 4, 0, 0.0, 0x3000, None) == -1

@@ -391,6 +391,45 @@ def test_advantages_group_shapes():
     assert none.numel() == 0
 
 
+@pytest.mark.parametrize("rows,V,groups,dtype,ws", [
+    (512, V_Q, 64, torch.bfloat16, None),      # one row per workgroup, groups ride along
+    (512, V_Q, 512, torch.bfloat16, None),     # as many groups as workgroups
+    (512, V_Q, 513, torch.bfloat16, None),     # one too many: own launch
+    (40, V_Q, 5, torch.bfloat16, None),        # small batch with a workspace: split path, own launch
+    (40, V_Q, 5, torch.float32, False),        # the same batch as whole rows
+    (3000, 4104, 700, torch.bfloat16, None),   # several rows per workgroup, fewer workgroups than rows
+    (5000, 20_000, 1, torch.float32, None),    # many rounds of workgroups, a single group
+])
+def test_advantages_riding_along_give_the_same_bits(rows, V, groups, dtype, ws):
+    g = torch.Generator(device=DEV).manual_seed(rows + groups)
+    lg = (torch.randn((rows, V), generator=g, device=DEV) * 3).to(dtype)
+    tgt = torch.randint(0, V, (rows,), generator=g, device=DEV).to(torch.int32)
+    tau = (0.6 + 0.8 * torch.rand(rows, generator=g, device=DEV)).float()
+    sizes = torch.randint(0, 12, (groups,), generator=g, device=DEV)
+    sizes[0] = 70                                           # longer than a wave
+    off = torch.zeros(groups + 1, dtype=torch.int32, device=DEV)
+    off[1:] = torch.cumsum(sizes, 0).to(torch.int32)
+    n = int(off[-1].item())
+    rew = (torch.rand(n, generator=g, device=DEV) < 0.4).float() + 0.25 * torch.rand(n, generator=g, device=DEV)
+    if groups > 1:
+        rew[off[1]:off[2]] = 1.0                            # a group of identical rewards
+    for ddof in (0, 1):
+        want_adv = e3.e3_grpo_advantages(rew, off, ddof, 1e-3)
+        want = e3.e3_logprob_entropy(lg, tgt, None, tau, 1.0, workspace=ws)
+        poison = torch.full((n,), float("nan"), device=DEV)
+        got = e3.e3_logprob_entropy_advantages(lg, tgt, None, tau, 1.0, rew, off, ddof, 1e-3,
+                                               adv_out=poison, workspace=ws)
+        torch.cuda.synchronize()
+        assert torch.equal(got[4], want_adv)
+        for x, y in zip(got[:4], want):
+            assert torch.equal(x, y)
+    ref = o.grpo_advantages(rew.cpu().numpy(), off.cpu().numpy(), 1, 1e-3)
+    assert np.abs(got[4].cpu().numpy() - ref).max() <= 1e-6
+    # no rows at all: the groups still get their advantages
+    empty = e3.e3_logprob_entropy_advantages(lg[:0], None, None, None, 1.0, rew, off, 1, 1e-3)
+    assert torch.equal(empty[4], want_adv)
+
+
 def test_many_short_rows():
     # 6000 rows x (1 complete + 1 incomplete super-tile): several rows per workgroup
     g = torch.Generator(device=DEV).manual_seed(12)
