@@ -242,7 +242,7 @@ static double row_tau(const float *tau_rows, float tau_scalar, int64_t r)
 /*
  * Rollout-side call: for every row, sample a token at temperature tau_r and
  * report its log-probability and the entropy of the tau-scaled distribution
- * (Section 5.1 "sampling temperature"; Appendix A softmax and entropy).
+ * (Section 5.1 fixes the temperature rollouts are drawn at; Appendix A softmax and entropy).
  * Outputs are double; near_tie_out and diag_out (4 doubles per row) nullable.
  * Returns 0, or -1 on allocation failure / bad arguments.
  */
@@ -673,7 +673,7 @@ int e3o_budget_bounds(int32_t G, int32_t passes_done, int32_t step, int32_t G_mi
  * Appendix A models a low-entropy row as one dominant logit z_max and all others a
  * common gap Delta below it, and notes that Delta could be estimated from the logits
  * (the paper then replaces it by ln N + ln ln N to avoid the extra pass).  Reading of
- * "estimate Delta from the logits": the probability-weighted mean gap of the
+ * that remark, which comes without a formula: the probability-weighted mean gap of the
  * non-maximal tokens,
  *     Delta_hat = sum_{i != i*} p_i (z_max - z_i) / sum_{i != i*} p_i,
  * i* = the first index attaining the maximum, p = softmax(z / tau).  It equals Delta

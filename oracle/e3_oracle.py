@@ -16,10 +16,6 @@ from . import build as _build
 
 F32, BF16 = 0, 1
 
-# Column partition of the two-level sampler that the HIP library fixes:
-# chunks of 8 columns dealt round-robin to 64 slots, 8 chunks of a slot per tile.
-LIB_PARTITION = (8, 64, 8)
-
 _lib = None
 
 
@@ -118,11 +114,11 @@ def gumbel(word: int) -> float:
     return float(lib().e3o_gumbel(word))
 
 
-def num_tiles(V: int, partition=LIB_PARTITION) -> int:
+def num_tiles(V: int, partition) -> int:
     return int(lib().e3o_num_tiles(V, *partition))
 
 
-def tile_of(col: int, partition=LIB_PARTITION) -> int:
+def tile_of(col: int, partition) -> int:
     return int(lib().e3o_tile_of(col, *partition))
 
 
@@ -153,8 +149,12 @@ class SampleResult:
 
 
 def sample_entropy(logits: np.ndarray, tau_rows: Optional[np.ndarray], tau_scalar: float,
-                   seed: int, row_base: int = 0, partition=LIB_PARTITION,
+                   seed: int, row_base: int = 0, *, partition,
                    nthreads: int = 1) -> SampleResult:
+    """partition = (chunk, lanes, depth) of the sampler's column tiles: columns are cut into
+    chunks, chunks dealt round-robin to `lanes` slots, a tile is `depth` successive chunks of
+    one slot.  It is part of the definition of the token and has no default here: a caller
+    states which sampler it means ((V, 1, 1) and (1, 1, 1) are the flat Gumbel-max)."""
     dt, rows, V, stride = _logits(logits)
     if tau_rows is not None:
         tau_rows = np.ascontiguousarray(tau_rows, dtype=np.float32)

@@ -13,6 +13,7 @@ from scipy.stats import chisquare
 
 from oracle import e3_oracle as o
 from tests import philox_np
+from tests.partition import LIB_PARTITION
 
 NT = 8  # oracle threads for the frequency tests
 
@@ -51,14 +52,16 @@ def test_matches_restatement_on_tiny_rows(partition):
 
 
 def test_library_partition_shape():
-    chunk, lanes, depth = o.LIB_PARTITION
+    chunk, lanes, depth = LIB_PARTITION
     assert (chunk, lanes, depth) == (8, 64, 8)
-    assert o.num_tiles(151_936) == 38 * 64 and o.num_tiles(1024) == 64 and o.num_tiles(4096) == 64
-    assert o.num_tiles(4097) == 128
+    nt = lambda V: o.num_tiles(V, LIB_PARTITION)
+    tile_of = lambda c: o.tile_of(c, LIB_PARTITION)
+    assert nt(151_936) == 38 * 64 and nt(1024) == 64 and nt(4096) == 64
+    assert nt(4097) == 128
     # columns 0..7 -> tile 0, 8..15 -> tile 1, ..., 504..511 -> tile 63, 512.. wraps to tile 0
-    assert [o.tile_of(c) for c in (0, 7, 8, 511, 512, 519, 4095, 4096, 4104)] == \
+    assert [tile_of(c) for c in (0, 7, 8, 511, 512, 519, 4095, 4096, 4104)] == \
         [0, 0, 1, 63, 0, 0, 63, 64, 65]
-    sizes = np.bincount([o.tile_of(c) for c in range(4096 + 100)], minlength=128)
+    sizes = np.bincount([tile_of(c) for c in range(4096 + 100)], minlength=128)
     assert (sizes[:64] == 64).all() and sizes[64:76].tolist() == [8] * 12 and sizes[76] == 4
 
 
@@ -93,7 +96,7 @@ def test_frequencies_library_partition_V1024():
     rng = np.random.default_rng(6)
     z = rng.normal(0, 2, 1024)
     z[[3, 500, 1000]] += 5.0
-    assert _freq_test(z, 1.0, o.LIB_PARTITION, 200_000, seed=13) > 1e-4
+    assert _freq_test(z, 1.0, LIB_PARTITION, 200_000, seed=13) > 1e-4
     assert _freq_test(z, 1.0, (1024, 1, 1), 200_000, seed=13) > 1e-4     # flat, same target law
 
 
@@ -110,13 +113,13 @@ def test_a_wrong_sampler_would_fail_the_frequency_test():
 def test_determinism_and_row_base():
     rng = np.random.default_rng(8)
     z = rng.normal(0, 2, (16, 700)).astype(np.float32)
-    a = o.sample_entropy(z, None, 1.0, seed=5, row_base=100)
-    b = o.sample_entropy(z, None, 1.0, seed=5, row_base=100, nthreads=4)
+    a = o.sample_entropy(z, None, 1.0, seed=5, row_base=100, partition=LIB_PARTITION)
+    b = o.sample_entropy(z, None, 1.0, seed=5, row_base=100, partition=LIB_PARTITION, nthreads=4)
     assert np.array_equal(a.token, b.token) and np.array_equal(a.logp, b.logp)
     # rows 8..15 sampled on their own with row_base moved = same tokens
-    c = o.sample_entropy(z[8:], None, 1.0, seed=5, row_base=108)
+    c = o.sample_entropy(z[8:], None, 1.0, seed=5, row_base=108, partition=LIB_PARTITION)
     assert np.array_equal(a.token[8:], c.token)
-    d = o.sample_entropy(z, None, 1.0, seed=6, row_base=100)
+    d = o.sample_entropy(z, None, 1.0, seed=6, row_base=100, partition=LIB_PARTITION)
     assert not np.array_equal(a.token, d.token)
     # logp and entropy agree with the training-side call on the sampled tokens
     t = o.logprob_entropy(z, a.token, None, None, 1.0)
@@ -161,7 +164,7 @@ def test_equal_masses_and_single_column_rows():
     res = o.sample_entropy(z, None, 1.0, seed=1, partition=(2, 2, 1))
     assert 0 <= res.token[0] < 4
     # degenerate one-column row
-    one = o.sample_entropy(np.array([[3.5]], np.float32), None, 0.5, seed=1)
+    one = o.sample_entropy(np.array([[3.5]], np.float32), None, 0.5, seed=1, partition=LIB_PARTITION)
     assert one.token[0] == 0 and one.logp[0] == 0.0 and one.entropy[0] == 0.0
     assert one.near_tie[0] == 0 and one.diag[0, 1] == -math.inf and one.diag[0, 3] == -math.inf
 
