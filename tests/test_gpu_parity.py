@@ -21,6 +21,7 @@ import torch
 import paper_2505_18573_amd as e3
 from oracle import e3_oracle as o
 from paper_2505_18573_amd import workloads as wl
+from tests.partition import LIB_PARTITION
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
@@ -54,7 +55,7 @@ def check_sample(logits, tau_rows, tau_scalar, seed, row_base, label):
     and without (whole rows per workgroup); both must match the oracle."""
     ref = o.sample_entropy(wl.host_bits(logits),
                            None if tau_rows is None else tau_rows.cpu().numpy(),
-                           tau_scalar, seed, row_base, nthreads=NT)
+                           tau_scalar, seed, row_base, partition=LIB_PARTITION, nthreads=NT)
     _check_sample_against(ref, logits, tau_rows, tau_scalar, seed, row_base, label + " [no ws]", False)
     return _check_sample_against(ref, logits, tau_rows, tau_scalar, seed, row_base, label, None)
 
@@ -83,39 +84,32 @@ def _check_sample_against(ref, logits, tau_rows, tau_scalar, seed, row_base, lab
     return ref, tok
 
 
-def check_logprob(logits, targets, mask, tau_rows, tau_scalar, label, rows_subset=None):
-    sel = slice(None) if rows_subset is None else rows_subset
-    sub = logits if rows_subset is None else logits[torch.as_tensor(rows_subset, device=logits.device)]
-    pick = (lambda t: None if t is None else t.cpu().numpy()[sel])
-    ref = o.logprob_entropy(wl.host_bits(sub), pick(targets), pick(mask), pick(tau_rows),
+def check_logprob(logits, targets, mask, tau_rows, tau_scalar, label):
+    pick = (lambda t: None if t is None else t.cpu().numpy())
+    ref = o.logprob_entropy(wl.host_bits(logits), pick(targets), pick(mask), pick(tau_rows),
                             tau_scalar, nthreads=NT)
     if e3.e3_workspace_bytes(logits.shape[0], logits.shape[1]) > 0:
-        _check_logprob_against(ref, sel, rows_subset, logits, targets, mask, tau_rows, tau_scalar,
-                               label + " [no ws]", False)
-    return _check_logprob_against(ref, sel, rows_subset, logits, targets, mask, tau_rows, tau_scalar,
-                                  label, None)
+        _check_logprob_against(ref, logits, targets, mask, tau_rows, tau_scalar, label + " [no ws]", False)
+    return _check_logprob_against(ref, logits, targets, mask, tau_rows, tau_scalar, label, None)
 
 
-def _check_logprob_against(ref, sel, rows_subset, logits, targets, mask, tau_rows, tau_scalar, label,
-                           workspace):
+def _check_logprob_against(ref, logits, targets, mask, tau_rows, tau_scalar, label, workspace):
     logp, ent, s, n = e3.e3_logprob_entropy(logits, targets, mask, tau_rows, tau_scalar,
                                             workspace=workspace)
     torch.cuda.synchronize()
-    assert_close(ent.cpu().numpy()[sel], ref.entropy, f"{label} entropy")
+    assert_close(ent.cpu().numpy(), ref.entropy, f"{label} entropy")
     if targets is not None:
-        got = logp.cpu().numpy()[sel]
+        got = logp.cpu().numpy()
         nan_ref = np.isnan(ref.logp)
         assert np.array_equal(np.isnan(got), nan_ref)
         assert_close(got[~nan_ref], ref.logp[~nan_ref], f"{label} logp")
-    # batch sum: against the library's own per-row output (all rows) ...
+    # batch sum: against the library's own per-row output and against the oracle's sum
     keep = torch.ones_like(ent, dtype=torch.bool) if mask is None else mask.bool()
     own = ent.double()[keep].sum().item()
     assert s.item() == pytest.approx(own, rel=1e-12, abs=1e-12)
     assert n.item() == int(keep.sum().item())
-    # ... and against the oracle when it saw every row
-    if rows_subset is None:
-        assert n.item() == ref.entropy_count
-        assert s.item() == pytest.approx(ref.entropy_sum, rel=1e-6, abs=1e-10 * max(1, n.item()))
+    assert n.item() == ref.entropy_count
+    assert s.item() == pytest.approx(ref.entropy_sum, rel=1e-6, abs=1e-10 * max(1, n.item()))
     return ref
 
 
@@ -187,13 +181,37 @@ def test_config3_dynamic_budgets_full_size():
 
 
 # ---------------------------------------------------------------- config 4
-def test_config4_training_pass_full_size_sampled_rows():
+def test_config4_training_pass_full_size_every_row():
+    # all 32,768 rows against the oracle (handed over in chunks of 4096 rows = 1.2 GB of host
+    # memory), and the two numbers behind H_t (Section 4.2, Eq. 4) at the full training size
     w = wl.training_pass(DEV)                                   # 32,768 x 151,936 bf16, ~10 GB
-    assert w.logits.shape == (32_768, V_Q)
-    subset = np.unique(np.concatenate([np.arange(0, 32_768, 64), [1, 32_767]]))
-    ref = check_logprob(w.logits, w.target_ids, None, None, 1.0, "cfg4", rows_subset=subset)
-    # mean entropy of N(0,3^2) logits at tau = 1 sits near ln V - 9/2
-    assert ref.entropy.mean() == pytest.approx(math.log(V_Q) - 4.5, abs=0.3)
+    rows = 32_768
+    assert w.logits.shape == (rows, V_Q)
+    logp, ent, s, n = e3.e3_logprob_entropy(w.logits, w.target_ids, None, None, 1.0)
+    torch.cuda.synchronize()
+    logp, ent = logp.cpu().numpy(), ent.cpu().numpy()
+    tgt = w.target_ids.cpu().numpy()
+    ref_ent = np.empty(rows)
+    ref_sum, ref_cnt = 0.0, 0
+    for r0 in range(0, rows, 4096):
+        r1 = r0 + 4096
+        ref = o.logprob_entropy(wl.host_bits(w.logits[r0:r1]), tgt[r0:r1], None, None, 1.0, nthreads=NT)
+        assert_close(ent[r0:r1], ref.entropy, f"cfg4 rows {r0}..{r1} entropy")
+        assert_close(logp[r0:r1], ref.logp, f"cfg4 rows {r0}..{r1} logp")
+        ref_ent[r0:r1] = ref.entropy
+        ref_sum += ref.entropy_sum                              # the oracle's own fp64 sums, chunk by chunk
+        ref_cnt += ref.entropy_count
+    assert n.item() == ref_cnt == rows
+    assert s.item() == pytest.approx(ref_sum, rel=1e-6)
+    assert s.item() == pytest.approx(float(ent.astype(np.float64).sum()), rel=1e-12)
+    print(f"[cfg4] batch-mean entropy: library {s.item() / n.item():.9f}  oracle {ref_sum / ref_cnt:.9f}")
+    # Sanity of the workload itself.  ln V - sigma^2 / (2 tau^2) = 7.431 is the V -> infinity
+    # value for N(0, 3^2) logits at tau = 1; at V = 151,936 the sum of exp(z) has not converged
+    # to its expectation (the terms that carry it lie 2 to 4 sigma out), which leaves the mean
+    # entropy at 7.523 +- 0.009 (fp64 numpy Monte Carlo over 3000 such rows, bf16-rounded, with
+    # the +6 target column; row-to-row standard deviation 0.51, so 32,768 rows add 0.003).
+    assert ref_ent.mean() == pytest.approx(7.523, abs=0.03)
+    assert ref_ent.mean() > math.log(V_Q) - 4.5
     del w
     torch.cuda.empty_cache()
 
@@ -320,7 +338,7 @@ def test_exact_ties_go_to_the_lowest_index_at_both_levels():
     for ws in (None, False):
         tok, _, _ = e3.e3_sample_entropy(z1, None, 1.0, seed=seed, row_base=row_id, workspace=ws)
         assert tok.item() == first_col_of_tile(t_lo) + 3
-    ref = o.sample_entropy(wl.host_bits(z1), None, 1.0, seed, row_id)
+    ref = o.sample_entropy(wl.host_bits(z1), None, 1.0, seed, row_id, partition=LIB_PARTITION)
     assert ref.token[0] == first_col_of_tile(t_lo) + 3 and ref.near_tie[0] == 1
     # level 2: two columns of one tile, V = 4096 (64 tiles of 64 columns); scan row ids
     cols = np.arange(4096)
@@ -342,7 +360,7 @@ def test_exact_ties_go_to_the_lowest_index_at_both_levels():
         tok, logp, _ = e3.e3_sample_entropy(z2, None, 1.0, seed=seed, row_base=row_id, workspace=ws)
         assert tok.item() == c_lo
         assert logp.item() == pytest.approx(math.log(0.5), rel=1e-5)
-    ref = o.sample_entropy(wl.host_bits(z2), None, 1.0, seed, row_id)
+    ref = o.sample_entropy(wl.host_bits(z2), None, 1.0, seed, row_id, partition=LIB_PARTITION)
     assert ref.token[0] == c_lo and ref.near_tie[0] == 1
 
 
@@ -455,7 +473,7 @@ def test_non_finite_inputs_give_nan_outputs_and_valid_tokens():
     tok = tok.cpu().numpy()
     assert ((tok >= 0) & (tok < 20_000)).all()
     clean = [0, 4, 7]
-    ref = o.sample_entropy(wl.host_bits(lg[clean]), None, 1.0, 1, 0)
+    ref = o.sample_entropy(wl.host_bits(lg[clean]), None, 1.0, 1, 0, partition=LIB_PARTITION)
     for j, r in enumerate(clean):                      # untouched rows are unaffected
         sub = e3.e3_sample_entropy(lg[r:r + 1], None, 1.0, seed=1, row_base=r)
         assert sub[0].item() == tok[r]
