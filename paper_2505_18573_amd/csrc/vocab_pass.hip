@@ -316,14 +316,20 @@ void vocab_pass_kernel(VocabPassArgs a, int rpb)
             RowPartial p;
             p.S = Sw; p.W = Ww; p.rc = s.rc; p.top = s.top; p.q = wb.q; p.tile = wb.idx;
             parts[r * (kWaves + 1) + slot] = p;
-            // LDS executes one wave's operations in order; keep the compiler from moving
-            // the write below the counter update (a fence would also drain the loads in flight)
-            asm volatile("" ::: "memory");
-            before = atomicAdd(&done[r], (uint32_t)n_items);
+            // Release: the partial is visible to the workgroup before the counter moves.
+            // The fence is restricted to the LDS address space, so it waits for this
+            // wave's LDS operations only and leaves its global loads in flight.
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+            before = __hip_atomic_fetch_add(&done[r], (uint32_t)n_items, __ATOMIC_RELAXED,
+                                            __HIP_MEMORY_SCOPE_WORKGROUP);
         }
         before = __builtin_amdgcn_readfirstlane(before);
-        if ((int)before + n_items == nst)
+        if ((int)before + n_items == nst) {
+            // Acquire: the counter said every other wave's partial of this row is written;
+            // order the reads of those partials behind it (LDS only, as above).
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
             finish_row<Chunk, kSample>(a, row0 + r, parts + r * (kWaves + 1), kWaves + 1, lane);
+        }
     };
     auto row_scale = [&](int r) -> float {
         const float tau = a.tau_rows ? a.tau_rows[row0 + r] : a.tau_scalar;
