@@ -4,6 +4,7 @@
 #include <cstdint>
 
 #include "../../include/e3.h"
+#include "../../include/e3_measure.h"
 #include "vocab_pass.h"
 
 namespace {
