@@ -41,10 +41,34 @@ ROWS = PROMPTS * ROLLOUTS
 HBM_PEAK_GBPS = 8000.0
 # algorithmic bytes of one sampled row: V bf16 logits + tau (4) read, token/logp/entropy (12) written
 BYTES_PER_ROW = V * 2 + 4 + 12
-# HBM bytes per launch of the sample kernel from rocprofv3 FETCH_SIZE + WRITE_SIZE, each scaled by
-# what the same counter reads for a device copy of known size (profiles/…hbm_traffic.txt).
-# Valid for the kernel as profiled; set to None when the kernel changes until re-measured.
-MEASURED_TRAFFIC_BYTES = 156_496_152
+TRAFFIC_RECORD = os.path.join(ROOT, "profiles", "vocab_pass_decode_step_hbm_traffic.txt")
+KERNEL_SOURCES = ("vocab_pass.hip", "vocab_common.h", "vocab_pass.h", "advantages.h")
+
+
+def kernel_source_sha256() -> str:
+    """Hash of the sources the vocabulary-pass kernels are compiled from."""
+    import hashlib
+    h = hashlib.sha256()
+    for name in KERNEL_SOURCES:
+        with open(os.path.join(ROOT, "paper_2505_18573_amd", "csrc", name), "rb") as f:
+            h.update(f.read())
+    return h.hexdigest()
+
+
+def measured_traffic_bytes():
+    """HBM bytes per launch of the sample kernel from rocprofv3 FETCH_SIZE + WRITE_SIZE, each
+    scaled by what the same counter reads for a device copy of known size.  The summary under
+    profiles/ records the figure together with the hash of the kernel sources it was taken
+    with; once the sources have changed the figure is stale and None is reported."""
+    import re
+    try:
+        text = open(TRAFFIC_RECORD).read()
+    except OSError:
+        return None
+    m = re.search(r"^traffic_bytes_per_launch sample: (\d+) kernel_sources_sha256: ([0-9a-f]{64})$", text, re.M)
+    if m is None or m.group(2) != kernel_source_sha256():
+        return None
+    return int(m.group(1))
 
 
 class DispatchEvents:
@@ -84,6 +108,9 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--buffers", type=int, default=8, help="distinct logit buffers rotated over")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-other-configs", action="store_true",
+                    help="skip the kernel timings on configs 3 (dynamic budgets), 4 (training pass) and "
+                         "5 (large decode batch) that the default run reports in `other_configs`")
     ap.add_argument("--restricted", action="store_true",
                     help="also time e3_sample_restricted (top-k 50, top-p 0.95) on the same batches and "
                          "report it in a `restricted_sampling` object; not part of the step")
@@ -94,7 +121,12 @@ def main() -> int:
                     help="also run a plain device copy of one logit buffer 10 times (a kernel of "
                          "known traffic: 155.6 MB read + 155.6 MB written) so that a rocprofv3 "
                          "--pmc run can scale FETCH_SIZE / WRITE_SIZE against it")
+    ap.add_argument("--kernel-sources-sha256", action="store_true",
+                    help="print the hash that a measured-traffic record under profiles/ is keyed to, and exit")
     args = ap.parse_args()
+    if args.kernel_sources_sha256:
+        print(kernel_source_sha256())
+        return 0
     if args.gpus != 1:
         print("bench.py measures one GPU: the path has no cross-GPU step (rows are independent); "
               "run with --gpus 1", file=sys.stderr)
@@ -218,7 +250,7 @@ def main() -> int:
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
-        "dtype": "f32",
+        "dtype": "f32 accumulation over bf16 logits",
         "data": "synthetic",
         "config": {
             "workload": "decode_step (config 2): 64 prompts x 8 rollouts = 512 rows, V=151936, "
@@ -236,7 +268,7 @@ def main() -> int:
         },
         "roofline": {
             "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-            "frac": achieved / HBM_PEAK_GBPS, "traffic": MEASURED_TRAFFIC_BYTES,
+            "frac": achieved / HBM_PEAK_GBPS, "traffic": measured_traffic_bytes(),
             "kernel": "vocab_pass_kernel<bf16, sample>",
         },
         "scheduler": {"tau_after": state["tau"], "H_init": state["H_init"]},
@@ -244,6 +276,14 @@ def main() -> int:
 
     out["read_ceiling"] = read_ceiling_leg(e3, batches, dev_events)
     out["roofline"]["frac_of_read_ceiling"] = achieved / out["read_ceiling"]["GBps"]
+    out["roofline"]["limiter"] = limiter(kern_avg_ms, out["read_ceiling"]["avg_ms"])
+    out["roofline"]["limiter_rule"] = LIMITER_RULE
+    if not args.no_other_configs:
+        keep = batches[0]
+        del batches
+        torch.cuda.empty_cache()
+        batches = [keep]
+        out["other_configs"] = other_configs_leg(e3, wl, dev, dev_events)
     if args.restricted:
         out["restricted_sampling"] = restricted_leg(e3, batches, stream)
     if args.sizes:
@@ -256,27 +296,127 @@ def main() -> int:
     return 0
 
 
+LIMITER_RULE = ("hbm when the kernel takes at most 1.05x the read-only probe on the same buffers (the memory "
+                "system sets its time), else valu (vector-ALU issue and the row epilogues hold it back; "
+                "rocprofv3 SQ counters under profiles/)")
+
+
+def limiter(kernel_ms: float, probe_ms: float) -> str:
+    return "hbm" if kernel_ms <= 1.05 * probe_ms else "valu"
+
+
+def timed_launches(e3, dev_events, fn, nbuf: int, reps: int):
+    """Average execution time (ms) of the vocabulary-pass dispatch inside fn(i), launched back
+    to back over rotating buffers, from events attached to the dispatch itself."""
+    warm = nbuf + 2                                  # every buffer once before timing
+    evs = [dev_events.pair() for _ in range(reps)]
+    for i in range(warm + reps):
+        if i >= warm:
+            e3.e3_time_next_launch(evs[i - warm][0].value, evs[i - warm][1].value)
+        fn(i)
+    torch.cuda.synchronize()
+    ms = sorted(dev_events.elapsed_ms(a, b) for a, b in evs)
+    dev_events.destroy(evs)
+    return sum(ms) / len(ms), ms[len(ms) // 2]
+
+
 def read_ceiling_leg(e3, batches, dev_events, reps: int = 50):
     """What a pure read of the same logit buffers reaches on this machine, timed exactly like
     the sample kernel (events attached to the dispatch, back-to-back launches, rotating
     buffers)."""
     dev = batches[0].logits.device
     sums = torch.empty(e3.binding.E3_READ_PROBE_SUMS, dtype=torch.int32, device=dev)
-    evs = [dev_events.pair() for _ in range(reps)]
-    for i in range(5 + reps):
-        b = batches[i % len(batches)]
-        if i >= 5:
-            e3.e3_time_next_launch(evs[i - 5][0].value, evs[i - 5][1].value)
-        e3.e3_read_probe(b.logits, sums)
-    torch.cuda.synchronize()
-    ms = sorted(dev_events.elapsed_ms(a, b) for a, b in evs)
-    dev_events.destroy(evs)
-    avg = sum(ms) / len(ms)
+    avg, med = timed_launches(e3, dev_events, lambda i: e3.e3_read_probe(batches[i % len(batches)].logits, sums),
+                              len(batches), reps)
     nbytes = ROWS * V * 2
     return {"kernel": "read_probe_kernel (16-byte non-temporal loads, 8-wave workgroups over contiguous "
                       "16-KiB runs, xor checksum only)",
-            "avg_ms": avg, "median_ms": ms[len(ms) // 2], "GBps": nbytes / (avg * 1e-3) / 1e9,
+            "avg_ms": avg, "median_ms": med, "GBps": nbytes / (avg * 1e-3) / 1e9,
             "frac_of_hbm_peak": nbytes / (avg * 1e-3) / 1e9 / HBM_PEAK_GBPS}
+
+
+def other_configs_leg(e3, wl, dev, dev_events):
+    """The vocabulary-pass kernel of each of the other full-size configurations on its own
+    generator's inputs: dynamic budgets (config 3: sample + entropy over 1024 rollouts, the
+    128 variable-size groups' advantages in a launch of their own), training pass (config 4:
+    log-prob of the target + entropy over 32,768 tokens, batch entropy sum), large decode
+    batch (config 5: 4096 rows at tau 0.3 / 2.0 with near-tied rows).  Back-to-back launches
+    over rotating buffers of more than 1 GB in total, dispatch events; the read-only probe on
+    the same buffers beside each."""
+    res = []
+    sums = torch.empty(e3.binding.E3_READ_PROBE_SUMS, dtype=torch.int32, device=dev)
+
+    def entry(name, kernel, rows, nbuf, reps, fn, probe_fn, extra=None):
+        nbytes = rows * (V * 2 + 4 + 12)
+        avg, med = timed_launches(e3, dev_events, fn, nbuf, reps)
+        p_avg, _ = timed_launches(e3, dev_events, probe_fn, nbuf, reps)
+        gbps = nbytes / (avg * 1e-3) / 1e9
+        e = {"config": name, "kernel": kernel, "rows": rows, "V": V, "logits_dtype": "bf16",
+             "kernel_avg_us": avg * 1e3, "kernel_median_us": med * 1e3, "rows_per_s": rows / (avg * 1e-3),
+             "GBps": gbps, "frac": gbps / HBM_PEAK_GBPS,
+             "read_probe_avg_us": p_avg * 1e3,
+             "read_probe_frac": rows * V * 2 / (p_avg * 1e-3) / 1e9 / HBM_PEAK_GBPS,
+             "limiter": limiter(avg, p_avg)}
+        if extra:
+            e.update(extra)
+        res.append(e)
+
+    # config 3: 1024 rollouts in 128 groups of 2..32
+    nbuf = 4
+    ws3 = [wl.dynamic_budgets(dev, seed=2 + i) for i in range(nbuf)]
+    rows = ws3[0].rows
+    tok = torch.empty(rows, dtype=torch.int32, device=dev)
+    lp = torch.empty(rows, dtype=torch.float32, device=dev)
+    en = torch.empty(rows, dtype=torch.float32, device=dev)
+    adv = torch.empty(rows, dtype=torch.float32, device=dev)
+    ws = e3.new_workspace(rows, V, dev)
+    a0, a1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    for i in range(3):
+        e3.e3_grpo_advantages(ws3[0].rewards, ws3[0].group_offsets, 0, 0.0, adv_out=adv)
+    a0.record()
+    for i in range(20):
+        e3.e3_grpo_advantages(ws3[i % nbuf].rewards, ws3[i % nbuf].group_offsets, 0, 0.0, adv_out=adv)
+    a1.record()
+    torch.cuda.synchronize()
+    entry("dynamic_budgets (config 3)", "vocab_pass_kernel<bf16, sample>", rows, nbuf, 40,
+          lambda i: e3.e3_sample_entropy(ws3[i % nbuf].logits, ws3[i % nbuf].tau_rows, 1.0, seed=2, row_base=i * rows,
+                                         token_out=tok, logp_out=lp, entropy_out=en, workspace=ws),
+          lambda i: e3.e3_read_probe(ws3[i % nbuf].logits, sums),
+          {"advantages_launch_us": a0.elapsed_time(a1) * 1e3 / 20, "groups": 128})
+    del ws3
+    torch.cuda.empty_cache()
+
+    # config 5: 4096 rows, tau in {0.3, 2.0}, 10 % near-tied rows
+    nbuf = 2
+    ws5 = [wl.large_decode(dev, seed=4 + i) for i in range(nbuf)]
+    rows = ws5[0].rows
+    tok = torch.empty(rows, dtype=torch.int32, device=dev)
+    lp = torch.empty(rows, dtype=torch.float32, device=dev)
+    en = torch.empty(rows, dtype=torch.float32, device=dev)
+    entry("large_decode (config 5)", "vocab_pass_kernel<bf16, sample>", rows, nbuf, 30,
+          lambda i: e3.e3_sample_entropy(ws5[i % nbuf].logits, ws5[i % nbuf].tau_rows, 1.0, seed=4, row_base=i * rows,
+                                         token_out=tok, logp_out=lp, entropy_out=en, workspace=False),
+          lambda i: e3.e3_read_probe(ws5[i % nbuf].logits, sums))
+    del ws5
+    torch.cuda.empty_cache()
+
+    # config 4: 32,768 response tokens (9.96 GB, far beyond every cache: one buffer)
+    w4 = wl.training_pass(dev)
+    rows = w4.rows
+    lp = torch.empty(rows, dtype=torch.float32, device=dev)
+    en = torch.empty(rows, dtype=torch.float32, device=dev)
+    hs = torch.empty(1, dtype=torch.float64, device=dev)
+    hc = torch.empty(1, dtype=torch.int64, device=dev)
+    entry("training_pass (config 4)", "vocab_pass_kernel<bf16, logprob>", rows, 1, 10,
+          lambda i: e3.e3_logprob_entropy(w4.logits, w4.target_ids, None, None, 1.0, logp_out=lp, entropy_out=en,
+                                          entropy_sum_out=hs, entropy_count_out=hc, workspace=False),
+          lambda i: e3.e3_read_probe(w4.logits, sums),
+          {"batch_mean_entropy": None})
+    torch.cuda.synchronize()
+    res[-1]["batch_mean_entropy"] = hs.item() / max(1, hc.item())
+    del w4
+    torch.cuda.empty_cache()
+    return res
 
 
 def sizes_leg(e3, dev, dev_events, reps: int = 40):
@@ -354,18 +494,20 @@ def restricted_leg(e3, batches, stream, reps: int = 50):
 def cpu_baseline(batch, rewards, offsets):
     """The oracle as it stands, timed on this machine's host cores over the same step."""
     from oracle import e3_oracle as o
+    from paper_2505_18573_amd import binding as e3b
     from paper_2505_18573_amd import workloads as wl
 
     threads = max(1, min(16, os.cpu_count() or 1, o.max_threads()))
+    part = (e3b.E3_TILE_CHUNK, e3b.E3_TILE_LANES, e3b.E3_TILE_DEPTH)   # the sampler the library fixes
     bits = wl.host_bits(batch.logits)
     tau = batch.tau_rows.cpu().numpy()
     r = rewards.cpu().numpy()
     off = offsets.cpu().numpy()
     reps = 10
-    o.sample_entropy(bits[:threads], tau[:threads], 1.0, 99, 0, nthreads=threads)   # warm the pages
+    o.sample_entropy(bits[:threads], tau[:threads], 1.0, 99, 0, partition=part, nthreads=threads)   # warm the pages
     t0 = time.perf_counter()
     for k in range(reps):
-        s = o.sample_entropy(bits, tau, 1.0, 99, k * ROWS, nthreads=threads)
+        s = o.sample_entropy(bits, tau, 1.0, 99, k * ROWS, partition=part, nthreads=threads)
         o.grpo_advantages(r, off)
         lp = o.logprob_entropy(bits, s.token, None, tau, 1.0, nthreads=threads)
         o.temperature_update(1.0, lp.entropy_mean, lp.entropy_mean, V)
@@ -373,12 +515,14 @@ def cpu_baseline(batch, rewards, offsets):
     # the same step on one thread, over the first 64 rows (8 groups)
     n1 = 64
     t0 = time.perf_counter()
-    s1 = o.sample_entropy(bits[:n1], tau[:n1], 1.0, 99, 0, nthreads=1)
+    s1 = o.sample_entropy(bits[:n1], tau[:n1], 1.0, 99, 0, partition=part, nthreads=1)
     o.grpo_advantages(r[:n1], off[:n1 // ROLLOUTS + 1])
     o.logprob_entropy(bits[:n1], s1.token, None, tau[:n1], 1.0, nthreads=1)
     dt1 = time.perf_counter() - t0
     return {
-        "value": ROWS * reps / dt, "unit": "rows/s", "cores": threads, "kind": "oracle",
+        "value": ROWS * reps / dt, "unit": "rows/s", "cores": threads, "host_cpus": os.cpu_count(),
+        "cores_note": "threads the oracle ran on: at most 16, this box's CPU share, whatever os.cpu_count() shows",
+        "kind": "oracle",
         "sample": f"{reps} full steps of the same 512-row batch ({ROWS * reps} rows), fp64, "
                   f"OpenMP over rows",
         "seconds": dt,
