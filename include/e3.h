@@ -36,7 +36,7 @@ typedef enum {
     E3_ERR_DTYPE = -3,     /* dtype is not an e3_dtype */
     E3_ERR_ALIGN = -4,     /* logits base or row pitch not 16-byte aligned */
     E3_ERR_VALUE = -5,     /* a scalar is outside its domain (tau <= 0, H <= 0, ...) */
-    E3_ERR_WORKSPACE = -6, /* reserved: the workspace is optional, no entry point returns this */
+    E3_ERR_WORKSPACE = -6, /* e3_sample_entropy_noalloc only: more rows than its scratch serves */
     E3_ERR_LAUNCH = -7     /* the HIP runtime refused a launch (see hipGetLastError) */
 } e3_status;
 
@@ -117,6 +117,28 @@ int e3_sample_entropy(const void* logits, int dtype, int64_t rows, int64_t V, in
                       uint64_t seed, uint64_t row_base,
                       int32_t* token_out, float* logp_out, float* entropy_out,
                       void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
+ * e3_sample_entropy for callers that cannot allocate device memory and therefore cannot
+ * bring the optional workspace: code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc.  Same arguments (without the workspace pair), same
+ * results bit for bit as e3_sample_entropy with a workspace of e3_workspace_bytes(rows, V):
+ * the small-batch path stages its 32-byte row partials in a 2 MiB array that the library
+ * holds in device memory for the life of the process (one copy per GPU it runs on, found
+ * on this entry point's first call on that GPU).  The call allocates and frees nothing.
+ *   rows  at most E3_NOALLOC_MAX_ROWS (what the array serves), else E3_ERR_WORKSPACE and
+ *         nothing is launched; larger batches need no scratch at all: call
+ *         e3_sample_entropy with workspace NULL.
+ * All calls on one GPU share the array: calls that can overlap there (different streams,
+ * different host threads) race on it and must be ordered by the caller; the array holds
+ * no state between calls (every slot is written before it is read).
+ */
+#define E3_NOALLOC_MAX_ROWS 1024
+int e3_sample_entropy_noalloc(const void* logits, int dtype, int64_t rows, int64_t V,
+                              int64_t row_stride, const float* tau_rows, float tau_scalar,
+                              uint64_t seed, uint64_t row_base,
+                              int32_t* token_out, float* logp_out, float* entropy_out,
+                              void* hip_stream);
 
 /*
  * Rollout-side call with truncation: sample one token per row from the temperature-

@@ -19,8 +19,10 @@ LIB_PATH = os.path.join(HERE, "libe3.so")
 E3_F32, E3_BF16 = 0, 1
 E3_OK = 0
 E3_TILE_CHUNK, E3_TILE_LANES, E3_TILE_DEPTH = 8, 64, 8
+E3_NOALLOC_MAX_ROWS = 1024
 
-EXPORTS = ("e3_strerror", "e3_workspace_bytes", "e3_sample_entropy", "e3_sample_restricted",
+EXPORTS = ("e3_strerror", "e3_workspace_bytes", "e3_sample_entropy", "e3_sample_entropy_noalloc",
+           "e3_sample_restricted",
            "e3_logprob_entropy", "e3_logprob_entropy_advantages",
            "e3_grpo_advantages", "e3_temperature_update", "e3_difficulty_ranks",
            "e3_allocate_budgets", "e3_budget_bounds", "e3_logprob_entropy_gap",
@@ -52,6 +54,8 @@ def lib() -> C.CDLL:
         L.e3_sample_entropy.argtypes = [vp, C.c_int, i64, i64, i64, vp, f32, u64, u64,
                                         vp, vp, vp, vp, C.c_size_t, vp]
         L.e3_sample_entropy.restype = C.c_int
+        L.e3_sample_entropy_noalloc.argtypes = [vp, C.c_int, i64, i64, i64, vp, f32, u64, u64, vp, vp, vp, vp]
+        L.e3_sample_entropy_noalloc.restype = C.c_int
         L.e3_sample_restricted.argtypes = [vp, C.c_int, i64, i64, i64, vp, f32, i32, f32, u64, u64,
                                            vp, vp, vp, vp]
         L.e3_sample_restricted.restype = C.c_int
@@ -183,6 +187,25 @@ def e3_sample_entropy(logits: torch.Tensor, tau_rows: Optional[torch.Tensor], ta
                                  _ptr(ws), ws_bytes, _stream(dev))
     if rc != E3_OK:
         raise E3Error(rc, "e3_sample_entropy")
+    return token_out, logp_out, entropy_out
+
+
+def e3_sample_entropy_noalloc(logits: torch.Tensor, tau_rows: Optional[torch.Tensor], tau_scalar: float,
+                              seed: int, row_base: int, token_out: torch.Tensor,
+                              logp_out: Optional[torch.Tensor], entropy_out: Optional[torch.Tensor]):
+    """The allocation-free entry point: the caller passes every output (nothing is allocated
+    here either).  Returns (token_out, logp_out, entropy_out)."""
+    dt, rows, V, stride = _logits_meta(logits)
+    dev = logits.device
+    _check(tau_rows, torch.float32, rows, "tau_rows", dev)
+    _check(token_out, torch.int32, rows, "token_out", dev)
+    _check(logp_out, torch.float32, rows, "logp_out", dev)
+    _check(entropy_out, torch.float32, rows, "entropy_out", dev)
+    rc = lib().e3_sample_entropy_noalloc(_ptr(logits), dt, rows, V, stride, _ptr(tau_rows),
+                                         float(tau_scalar), int(seed), int(row_base),
+                                         _ptr(token_out), _ptr(logp_out), _ptr(entropy_out), _stream(dev))
+    if rc != E3_OK:
+        raise E3Error(rc, "e3_sample_entropy_noalloc")
     return token_out, logp_out, entropy_out
 
 

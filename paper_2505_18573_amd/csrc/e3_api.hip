@@ -40,7 +40,7 @@ extern "C" const char* e3_strerror(int status)
         case E3_ERR_DTYPE: return "unknown dtype";
         case E3_ERR_ALIGN: return "logits base or row pitch is not 16-byte aligned";
         case E3_ERR_VALUE: return "scalar argument outside its domain";
-        case E3_ERR_WORKSPACE: return "workspace missing or too small";
+        case E3_ERR_WORKSPACE: return "batch exceeds what the library-owned scratch holds";
         case E3_ERR_LAUNCH: return "HIP launch failed";
         default: return "unknown status";
     }
@@ -71,6 +71,34 @@ extern "C" int e3_sample_entropy(const void* logits, int dtype, int64_t rows, in
     a.target_ids = nullptr;
     a.token_out = token_out; a.logp_out = logp_out; a.entropy_out = entropy_out;
     hipError_t err = e3::launch_vocab_pass(a, dtype == E3_BF16, true, workspace, workspace_bytes,
+                                           static_cast<hipStream_t>(hip_stream));
+    return err == hipSuccess ? E3_OK : E3_ERR_LAUNCH;
+}
+
+extern "C" int e3_sample_entropy_noalloc(const void* logits, int dtype, int64_t rows, int64_t V,
+                                         int64_t row_stride, const float* tau_rows, float tau_scalar,
+                                         uint64_t seed, uint64_t row_base,
+                                         int32_t* token_out, float* logp_out, float* entropy_out,
+                                         void* hip_stream)
+{
+    int rc = check_logits(logits, dtype, rows, V, row_stride);
+    if (rc != E3_OK) return rc;
+    rc = check_tau(tau_rows, tau_scalar);
+    if (rc != E3_OK) return rc;
+    if (rows > e3::static_scratch_max_rows()) return E3_ERR_WORKSPACE;
+    if (rows == 0) return E3_OK;
+    if (token_out == nullptr) return E3_ERR_NULL;
+    void* ws = nullptr;
+    size_t ws_bytes = 0;
+    if (e3::static_scratch(&ws, &ws_bytes) != hipSuccess) return E3_ERR_LAUNCH;
+
+    e3::VocabPassArgs a{};
+    a.logits = logits; a.rows = rows; a.V = V; a.row_stride = row_stride;
+    a.tau_rows = tau_rows; a.tau_scalar = tau_scalar;
+    a.seed = seed; a.row_base = row_base;
+    a.target_ids = nullptr;
+    a.token_out = token_out; a.logp_out = logp_out; a.entropy_out = entropy_out;
+    hipError_t err = e3::launch_vocab_pass(a, dtype == E3_BF16, true, ws, ws_bytes,
                                            static_cast<hipStream_t>(hip_stream));
     return err == hipSuccess ? E3_OK : E3_ERR_LAUNCH;
 }

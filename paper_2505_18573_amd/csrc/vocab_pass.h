@@ -41,6 +41,12 @@ LaunchEvents take_launch_events();
 // upper bound of the workspace the small-batch path can use for this shape (0: none)
 size_t vocab_pass_workspace_bytes(int64_t rows, int64_t V);
 
+// Library-owned scratch (a file-scope device array) that stands in for the caller workspace:
+// address of the current device's copy and its size; rows beyond static_scratch_max_rows()
+// are not served from it.  Looks the address up on the first call on a device.
+hipError_t static_scratch(void** ptr_out, size_t* bytes_out);
+int64_t static_scratch_max_rows();
+
 // false when V is so large that the per-workgroup tables do not fit LDS
 bool vocab_pass_fits(int64_t V);
 

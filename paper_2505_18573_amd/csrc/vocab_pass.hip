@@ -28,6 +28,7 @@
 #include "vocab_common.h"
 #include "vocab_pass.h"
 #include <hip/hip_ext.h>
+#include <mutex>
 
 namespace e3 {
 
@@ -748,6 +749,41 @@ hipError_t launch_vocab_pass(const VocabPassArgs& args, bool is_bf16, bool sampl
                       : launch_for<ChunkBf16, false>(a, stream);
     return sample ? launch_for<ChunkF32, true>(a, stream)
                   : launch_for<ChunkF32, false>(a, stream);
+}
+
+// ---------------------------------------------------------------------------
+// Library-owned scratch for callers that cannot allocate: the small-batch path's row
+// partials in a file-scope device array instead of a caller workspace.  Every GPU the
+// library runs on holds its own copy of the array at its own address, looked up once
+// per device; host code uses that address, never the array's name.
+// ---------------------------------------------------------------------------
+constexpr size_t kStaticScratchBytes = (size_t)kSplitMaxRows * 64 * sizeof(RowPartial);   // 2 MiB
+static_assert(kStaticScratchBytes == 2u * 1024 * 1024, "documented size");
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+constexpr int kMaxDevices = 64;
+static std::mutex g_scratch_mutex;
+static void* g_scratch_ptr[kMaxDevices] = {};
+
+int64_t static_scratch_max_rows() { return kSplitMaxRows; }
+
+hipError_t static_scratch(void** ptr_out, size_t* bytes_out)
+{
+    int dev = -1;
+    hipError_t err = hipGetDevice(&dev);
+    if (err != hipSuccess) return err;
+    if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (g_scratch_ptr[dev] == nullptr) {
+        void* p = nullptr;
+        err = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));     // this device's copy
+        if (err != hipSuccess) return err;
+        if (p == nullptr) return hipErrorInvalidSymbol;
+        g_scratch_ptr[dev] = p;
+    }
+    *ptr_out = g_scratch_ptr[dev];
+    *bytes_out = kStaticScratchBytes;
+    return hipSuccess;
 }
 
 hipError_t launch_entropy_reduce(const float* entropy, const uint8_t* mask, int64_t rows,

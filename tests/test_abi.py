@@ -75,6 +75,19 @@ def test_sample_entropy_argument_checks_precede_any_launch():
     assert _sample(rows=0, logits=None, tok=None) == 0       # empty batch is a no-op
 
 
+def test_noalloc_entry_point_checks_and_row_limit():
+    L = e3.lib()
+    def call(logits=0x1000, dtype=1, rows=4, V=64, stride=64, tau=1.0, tok=0x2000):
+        return L.e3_sample_entropy_noalloc(logits, dtype, rows, V, stride, None, tau, 1, 0, tok, None, None, None)
+    assert call(dtype=9) == -3 and call(V=0) == -2 and call(logits=0x1004) == -4 and call(tau=0.0) == -5
+    assert call(rows=e3.binding.E3_NOALLOC_MAX_ROWS + 1) == -6        # E3_ERR_WORKSPACE, before any launch
+    assert call(rows=0, logits=None, tok=None) == 0
+    text = open(os.path.join(ROOT, "include", "e3.h")).read()
+    assert int(re.search(r"#define E3_NOALLOC_MAX_ROWS (\d+)", text).group(1)) == e3.binding.E3_NOALLOC_MAX_ROWS
+    # what the array must hold for the largest batch it serves
+    assert e3.e3_workspace_bytes(e3.binding.E3_NOALLOC_MAX_ROWS, 2_000_000) == 2 * 1024 * 1024
+
+
 def test_logprob_entropy_argument_checks():
     L = e3.lib()
     def call(logits=0x1000, dtype=0, rows=4, V=64, stride=64, tgt=0x3000, tau=1.0,
