@@ -95,6 +95,35 @@ __device__ __forceinline__ float wave_max(float v)
     return last_lane(v);
 }
 
+// The same over lanes 0..15 only (one DPP row): four butterfly steps leave the row's maximum
+// in each of its lanes; lane 0 is read.  For reductions whose operands live in the first
+// sixteen lanes (a row's few partials, the sixteen lanes of the sampler's second level).
+__device__ __forceinline__ float row16_max(float v)
+{
+    asm("s_nop 1\n\t"
+        "v_max_f32_dpp %0, %0, %0 quad_perm:[1,0,3,2] row_mask:0xf bank_mask:0xf\n\t"
+        "s_nop 1\n\t"
+        "v_max_f32_dpp %0, %0, %0 quad_perm:[2,3,0,1] row_mask:0xf bank_mask:0xf\n\t"
+        "s_nop 1\n\t"
+        "v_max_f32_dpp %0, %0, %0 row_half_mirror row_mask:0xf bank_mask:0xf\n\t"
+        "s_nop 1\n\t"
+        "v_max_f32_dpp %0, %0, %0 row_mirror row_mask:0xf bank_mask:0xf\n\t"
+        "s_nop 1"
+        : "+v"(v));
+    return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 0));
+}
+
+__device__ __forceinline__ double row16_sum(double v)
+{
+    v += dpp_d<kDppXor1>(0.0, v);
+    v += dpp_d<kDppXor2>(0.0, v);
+    v += dpp_d<kDppHalfMirror>(0.0, v);
+    v += dpp_d<kDppMirror>(0.0, v);
+    const int lo = __builtin_amdgcn_readlane(__double2loint(v), 0);
+    const int hi = __builtin_amdgcn_readlane(__double2hiint(v), 0);
+    return __hiloint2double(hi, lo);
+}
+
 // Sum over the wave in fp64, returned wave-uniform.
 __device__ __forceinline__ double wave_sum(double v)
 {
@@ -155,6 +184,19 @@ __device__ __forceinline__ Cand wave_best(Cand c)
     Cand r;
     r.q = last_lane(c.q);
     r.idx = __builtin_amdgcn_readlane(c.idx, 63);
+    return r;
+}
+
+// Best candidate among lanes 0..15, returned wave-uniform.
+__device__ __forceinline__ Cand row16_best(Cand c)
+{
+    c = best_step<kDppXor1>(c);
+    c = best_step<kDppXor2>(c);
+    c = best_step<kDppHalfMirror>(c);
+    c = best_step<kDppMirror>(c);
+    Cand r;
+    r.q = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(c.q), 0));
+    r.idx = __builtin_amdgcn_readlane(c.idx, 0);
     return r;
 }
 

@@ -54,8 +54,12 @@ __host__ __device__ inline size_t lds_bytes(int rpb, int nst, bool sample)
 
 // Row epilogue, run by one wave once all of the row's partials are written: merge the
 // partials (one per lane, nparts <= 64), level 2 of the sampler or the target gather,
-// outputs.
-template <typename Chunk, bool kSample>
+// outputs.  kFew: the partials sit in the first sixteen lanes (a row-block workgroup hands
+// over at most nine), so every reduction over them is four DPP steps inside one row of lanes
+// instead of six across the wave; level 2 always works on sixteen lanes.  This wave's work
+// is a chain of dependent instructions that nothing overlaps once the row is the last of the
+// launch, hence the care to keep it short.
+template <typename Chunk, bool kSample, bool kFew>
 __device__ __forceinline__ void finish_row(const VocabPassArgs& a, int64_t row,
                                            const RowPartial* parts, int nparts, int lane)
 {
@@ -80,8 +84,8 @@ __device__ __forceinline__ void finish_row(const VocabPassArgs& a, int64_t row,
     // R is the common reference, `peak` the largest logit of the row; the partial
     // that holds it is the lowest lane with that top, every other excluded maximum
     // joins the rest as an ordinary term.
-    const float R = wave_max(p.rc);
-    const float peak = wave_max(p.top);
+    const float R = kFew ? row16_max(p.rc) : wave_max(p.rc);
+    const float peak = kFew ? row16_max(p.top) : wave_max(p.top);
     const unsigned long long holders = __ballot(p.top == peak);
     const int peak_lane = (int)__builtin_ctzll(holders | (1ull << 63));
     const bool live = p.rc > -INFINITY;
@@ -97,7 +101,8 @@ __device__ __forceinline__ void finish_row(const VocabPassArgs& a, int64_t row,
     uint32_t w[4] = {0u, 0u, 0u, 0u};
     int64_t col0 = 0;
     if (kSample) {
-        const Cand win = wave_best(Cand{live ? ldexpf(p.q, sh) : -1.0f, p.tile});
+        const Cand mine{live ? ldexpf(p.q, sh) : -1.0f, p.tile};
+        const Cand win = kFew ? row16_best(mine) : wave_best(mine);
         const int wst = win.idx / kLanes, wslot = win.idx % kLanes;
         // 2 * kDepth lanes x 4 consecutive columns cover the tile
         col0 = (int64_t)wst * kSuperCols + (int64_t)(lane >> 1) * kSweepCols
@@ -124,8 +129,8 @@ __device__ __forceinline__ void finish_row(const VocabPassArgs& a, int64_t row,
             W_l += tw * ew;
         }
     }
-    const double S_rest = wave_sum(S_l);
-    const double W_rest = wave_sum(W_l);
+    const double S_rest = kFew ? row16_sum(S_l) : wave_sum(S_l);
+    const double W_rest = kFew ? row16_sum(W_l) : wave_sum(W_l);
     // With e_p = 2^{t_p} the peak's term, x = S_rest / e_p and y = W_rest / e_p:
     //   ln S = t_p ln2 + log1p(x),   H = ln S - ln2 W / S = log1p(x) + ln2 (t_p x - y) / (1 + x),
     // every piece of which is O(x) when the row is peaked.  t_p lies in (-1, 0].
@@ -135,32 +140,6 @@ __device__ __forceinline__ void finish_row(const VocabPassArgs& a, int64_t row,
     const double l1p = (double)log1pf((float)x);
     const double H = l1p + kLn2 * (t_p * x - y) / (1.0 + x);
 
-    int64_t tok;
-    float z_tok;
-    if (kSample) {
-        // Level 2: Gumbel-max inside the winning tile, in race form: maximise
-        // 2^{(z - zmax) c} / E_col.
-        const float zmax = wave_max(fmaxf(fmaxf(cz[0], cz[1]), fmaxf(cz[2], cz[3])));
-        Cand cb{-1.0f, 0x7FFFFFFF};
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const bool ok = lane < 2 * kDepth && col0 + j < V;
-            const float q = __builtin_amdgcn_exp2f((cz[j] - zmax) * c) * inv_e2[j];
-            cb = better(cb, Cand{ok ? q : -1.0f, ok ? (int)(col0 + j) : 0x7FFFFFFF});
-        }
-        cb = wave_best(cb);
-        tok = cb.idx;
-        if (tok < 0 || tok >= V) tok = 0;                 // only reachable with non-finite input
-        float own = -INFINITY;
-#pragma unroll
-        for (int j = 0; j < 4; ++j)
-            if (col0 + j == tok) own = cz[j];
-        z_tok = wave_max(own);
-        if (lane == 0) a.token_out[row] = (int32_t)tok;
-    } else {
-        tok = tgt;
-        z_tok = z_tgt;
-    }
     if (lane == 0) {
         if (a.entropy_out) a.entropy_out[row] = (float)H;
         if (a.gap_out) {
@@ -169,12 +148,40 @@ __device__ __forceinline__ void finish_row(const VocabPassArgs& a, int64_t row,
             a.gap_out[row] = S_rest > 0.0 ? (float)((double)tau * kLn2 * (t_p - W_rest / S_rest))
                                           : __builtin_nanf("");
         }
-        if (a.logp_out) {
-            float lp = __builtin_nanf("");
-            if (tok >= 0 && tok < V)   // ln p = (a_tok - a_peak) - log1p(x)
-                lp = (float)(((double)z_tok - (double)peak) * cd * kLn2 - l1p);
-            a.logp_out[row] = lp;
+    }
+    if (kSample) {
+        // Level 2: Gumbel-max inside the winning tile, in race form: maximise
+        // 2^{(z - z_peak) c} / E_col.  The row's peak serves as the reference: the winning
+        // tile's largest column lies within 2^-34 of it (a tile further down cannot make up
+        // the difference with its noise, whose range is 2^-24 .. 17), far from underflow.
+        Cand cb{-1.0f, 0x7FFFFFFF};
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const bool ok = lane < 2 * kDepth && col0 + j < V;
+            const float q = __builtin_amdgcn_exp2f((cz[j] - peak) * c) * inv_e2[j];
+            cb = better(cb, Cand{ok ? q : -1.0f, ok ? (int)(col0 + j) : 0x7FFFFFFF});
         }
+        cb = row16_best(cb);
+        int64_t tok = cb.idx;
+        if (tok < 0 || tok >= V) tok = 0;                 // only reachable with non-finite input
+        if (lane == 0) a.token_out[row] = (int32_t)tok;
+        // the lane that holds the token's column writes its log-probability:
+        //   ln p = (a_tok - a_peak) - log1p(x)
+        if (a.logp_out) {
+            const bool holder = lane < 2 * kDepth && cb.idx >= col0 && cb.idx < col0 + 4;
+            if (holder) {
+                const int j = (int)(cb.idx - col0);
+                const float z_tok = j == 0 ? cz[0] : j == 1 ? cz[1] : j == 2 ? cz[2] : cz[3];
+                a.logp_out[row] = (float)(((double)z_tok - (double)peak) * cd * kLn2 - l1p);
+            }
+            // no column won the race (non-finite logits): the row's outputs are NaN
+            if (__ballot(holder) == 0 && lane == 0) a.logp_out[row] = __builtin_nanf("");
+        }
+    } else if (lane == 0 && a.logp_out) {
+        float lp = __builtin_nanf("");
+        if (tgt >= 0 && tgt < V)
+            lp = (float)(((double)z_tgt - (double)peak) * cd * kLn2 - l1p);
+        a.logp_out[row] = lp;
     }
 }
 
@@ -329,7 +336,7 @@ void vocab_pass_kernel(VocabPassArgs a, int rpb)
             // Acquire: the counter said every other wave's partial of this row is written;
             // order the reads of those partials behind it (LDS only, as above).
             __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
-            finish_row<Chunk, kSample>(a, row0 + r, parts + r * (kWaves + 1), kWaves + 1, lane);
+            finish_row<Chunk, kSample, true>(a, row0 + r, parts + r * (kWaves + 1), kWaves + 1, lane);
         }
     };
     auto row_scale = [&](int r) -> float {
@@ -505,8 +512,8 @@ template <typename Chunk, bool kSample>
 __global__ __launch_bounds__(64)
 void row_finish_kernel(VocabPassArgs a, const RowPartial* __restrict__ ws, int nslots)
 {
-    finish_row<Chunk, kSample>(a, (int64_t)blockIdx.x, ws + (size_t)blockIdx.x * nslots, nslots,
-                               (int)threadIdx.x);
+    finish_row<Chunk, kSample, false>(a, (int64_t)blockIdx.x, ws + (size_t)blockIdx.x * nslots, nslots,
+                                      (int)threadIdx.x);
 }
 
 // ---------------------------------------------------------------------------
@@ -787,10 +794,15 @@ hipError_t static_scratch(void** ptr_out, size_t* bytes_out)
 }
 
 hipError_t launch_entropy_reduce(const float* entropy, const uint8_t* mask, int64_t rows,
-                                 double* sum_out, int64_t* count_out, hipStream_t stream)
+                                 double* sum_out, int64_t* count_out, hipStream_t stream,
+                                 hipEvent_t stop_event)
 {
-    hipLaunchKernelGGL(entropy_reduce_kernel, dim3(1), dim3(1024), 0, stream,
-                       entropy, mask, rows, sum_out, count_out);
+    if (stop_event != nullptr)
+        hipExtLaunchKernelGGL(entropy_reduce_kernel, dim3(1), dim3(1024), 0u, stream,
+                              (hipEvent_t) nullptr, stop_event, 0u, entropy, mask, rows, sum_out, count_out);
+    else
+        hipLaunchKernelGGL(entropy_reduce_kernel, dim3(1), dim3(1024), 0, stream,
+                           entropy, mask, rows, sum_out, count_out);
     return hipGetLastError();
 }
 
