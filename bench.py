@@ -16,9 +16,10 @@ Inputs are resident in HBM before timing starts.  The batch is 156 MB, smaller t
 the 256 MB memory-side cache, so the step rotates over enough distinct logit buffers
 that more than 1 GB is touched between two uses of the same buffer.
 
-Prints ONE JSON line.  `roofline` prices the sample kernel's algorithmic bytes against
-the 8 TB/s HBM peak using HIP events attached to the kernel's dispatch in every timed step;
-`read_ceiling` is a read-only kernel over the same buffers timed the same way;
+Prints ONE JSON line.  `value` comes from K plain steps; `roofline` prices the sample kernel's
+algorithmic bytes against the 8 TB/s HBM peak using HIP events attached to every dispatch in a
+second run of the same K steps; `read_ceiling` is a read-only kernel over the same buffers timed
+the same way; `other_configs` holds the kernel's figures on configs 3, 4 and 5;
 `cpu_baseline` times the CPU oracle on the same workload (reported, not a target).
 """
 from __future__ import annotations
@@ -176,15 +177,19 @@ def main() -> int:
 
     stats_ready = torch.cuda.Event()
 
-    def step(i: int, ev=None):
+    def step(i: int, ev=None, ev_train=None):
         """One cycle of the method: advantages, training pass on the previous rollouts (its
         mean entropy H_t goes to the host), next rollouts, scheduler.  The host waits only for
         the event behind the training pass, whose 16 bytes land in pinned host memory, so Eq. 4 / Eq. 5 run on the host
         while the rollout kernel is still executing; the temperature they produce is the one
         the following step's rollouts would use.  `ev`: a HIP event pair that the library
-        attaches to the sampling kernel's dispatch (begin and end of its execution)."""
+        attaches to the sampling kernel's dispatch (begin and end of its execution); `ev_train`:
+        the same for the training-side call (begin of its vocabulary pass, end of the reduction
+        kernel that follows it)."""
         roll = batches[i % nb]
         train = batches[(i + nb // 2) % nb]
+        if ev_train is not None:
+            e3.e3_time_next_launch(ev_train[0].value, ev_train[1].value)
         e3.e3_logprob_entropy_advantages(train.logits, tok, None, train.tau_rows, 1.0, rewards, offsets,
                                          0, 0.0, logp_out=logp_t, entropy_out=ent_t,
                                          entropy_sum_out=hsum, entropy_count_out=hcnt, adv_out=adv,
@@ -209,13 +214,28 @@ def main() -> int:
     torch.cuda.synchronize()
 
     dev_events = DispatchEvents()
-    events = [dev_events.pair() for _ in range(args.steps)]
+    # Timed region: K steps as a caller runs them, nothing attached.
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for i in range(args.steps):
-        step(args.warmup + i, events[i])
+        step(args.warmup + i)
     torch.cuda.synchronize()
     t1 = time.perf_counter()
+
+    # The same K steps once more with HIP events attached to every dispatch of the two calls,
+    # for the kernels' own durations.  They are kept out of the timed region because they are
+    # not free: an event-carrying dispatch costs the stream about 4 us (the step grows from
+    # ~67 to ~82 us with three of them), and a dispatch that follows a plain one is charged
+    # 1.5-2 us of its predecessor's retirement, so either every dispatch of the step carries
+    # events (as under a profiler's kernel trace) or none does.
+    events = [dev_events.pair() for _ in range(args.steps)]
+    events_train = [dev_events.pair() for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t2 = time.perf_counter()
+    for i in range(args.steps):
+        step(args.warmup + args.steps + i, events[i], events_train[i])
+    torch.cuda.synchronize()
+    t3 = time.perf_counter()
 
     # The same launches bracketed by marker events (torch.cuda.Event pairs recorded on the
     # stream), for reference: markers are packets of their own and read ~5 us more.
@@ -235,6 +255,8 @@ def main() -> int:
     rows_per_s = ROWS * args.steps / (t1 - t0)
     kern_ms = sorted(dev_events.elapsed_ms(a, b) for a, b in events)
     dev_events.destroy(events)
+    train_ms = sorted(dev_events.elapsed_ms(a, b) for a, b in events_train)
+    dev_events.destroy(events_train)
     kern_avg_ms = sum(kern_ms) / len(kern_ms)
     achieved = ROWS * BYTES_PER_ROW / (kern_avg_ms * 1e-3) / 1e9
 
@@ -247,6 +269,7 @@ def main() -> int:
         "steps": args.steps,
         "warmup": args.warmup,
         "ms_per_step": ms_per_step,
+        "ms_per_step_with_dispatch_events": (t3 - t2) * 1e3 / args.steps,
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
@@ -261,10 +284,18 @@ def main() -> int:
         "sample_kernel": {
             "avg_ms": kern_avg_ms, "median_ms": kern_ms[len(kern_ms) // 2], "min_ms": kern_ms[0],
             "rows_per_s": ROWS / (kern_avg_ms * 1e-3),
-            "timing": "HIP events attached to the kernel's dispatch (hipExtLaunchKernel start/stop "
-                      "events via e3_time_next_launch), every timed step",
+            "timing": "HIP events attached to the kernel's dispatch (hipExtLaunchKernel start/stop events via "
+                      "e3_time_next_launch) in a second run of the same K steps right after the timed region, "
+                      "in which every dispatch of the step carries events; the timed region itself runs "
+                      "without them (they cost the stream ~4 us per dispatch)",
             "marker_pair_avg_ms": sum(marker_ms) / len(marker_ms),
             "marker_pair_note": "the same launch bracketed by two recorded marker events instead",
+        },
+        "training_call": {
+            "avg_ms": sum(train_ms) / len(train_ms), "median_ms": train_ms[len(train_ms) // 2],
+            "what": "e3_logprob_entropy_advantages on the same shape: begin of the vocabulary pass (with the "
+                    "64 groups' advantages aboard) to the end of the batch-sum kernel that follows it, "
+                    "dispatch events, same instrumented run of the K steps as the sample kernel",
         },
         "roofline": {
             "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",

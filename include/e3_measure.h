@@ -18,8 +18,9 @@ extern "C" {
  * The next e3_sample_entropy / e3_logprob_entropy(_gap) / e3_read_probe
  * call made by this host thread attaches the two events (hipEvent_t created by the caller with timing
  * enabled; either may be NULL) to its vocabulary-pass dispatch: `start_event` then holds
- * the time the kernel began to execute and `stop_event` the time it ended (with a
- * workspace and a small batch: begin of the first of the two kernels, end of the second),
+ * the time the kernel began to execute and `stop_event` the time it ended (when the call
+ * launches more than one kernel -- a small batch with a workspace, a training-side call that
+ * also returns the batch sums -- begin of the first kernel and end of the last),
  * so hipEventElapsedTime gives the kernel's own duration without the cost of marker
  * packets recorded around it.  The hook is consumed by the first such call that reaches its
  * launch (a call rejected by its argument checks, or with rows == 0, leaves it in place);

@@ -29,6 +29,16 @@ int check_tau(const float* tau_rows, float tau_scalar)
     return (std::isfinite(tau_scalar) && tau_scalar > 0.0f) ? E3_OK : E3_ERR_VALUE;
 }
 
+// When a call's vocabulary pass is followed by a reduction kernel, the measurement hook's stop
+// event goes to that last kernel: take it out of the pending pair and leave the start event
+// for the vocabulary pass.
+hipEvent_t split_stop_event()
+{
+    const e3::LaunchEvents ev = e3::take_launch_events();
+    e3::set_launch_events(ev.start, nullptr);
+    return ev.stop;
+}
+
 }  // namespace
 
 extern "C" const char* e3_strerror(int status)
@@ -154,6 +164,10 @@ extern "C" int e3_logprob_entropy_gap(const void* logits, int dtype, int64_t row
     if (logp_out != nullptr && target_ids == nullptr) return E3_ERR_NULL;
     if (gap_sum_out != nullptr && gap_out == nullptr) return E3_ERR_NULL;
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    const bool h_sum = entropy_sum_out != nullptr || count_out != nullptr, g_sum = gap_sum_out != nullptr;
+    // measurement hook: the stop event belongs to the call's last kernel
+    hipEvent_t stop_last = nullptr;
+    if (rows > 0 && (h_sum || g_sum)) stop_last = split_stop_event();
 
     if (rows > 0) {
         e3::VocabPassArgs a{};
@@ -167,13 +181,14 @@ extern "C" int e3_logprob_entropy_gap(const void* logits, int dtype, int64_t row
             return E3_ERR_LAUNCH;
     }
     // also for rows == 0: sums and count are then written as 0
-    if (entropy_sum_out != nullptr || count_out != nullptr) {
+    if (h_sum) {
         if (e3::launch_entropy_reduce(entropy_out, row_mask, rows, entropy_sum_out, count_out,
-                                      stream) != hipSuccess)
+                                      stream, g_sum ? nullptr : stop_last) != hipSuccess)
             return E3_ERR_LAUNCH;
     }
-    if (gap_sum_out != nullptr) {
-        if (e3::launch_entropy_reduce(gap_out, row_mask, rows, gap_sum_out, nullptr, stream) != hipSuccess)
+    if (g_sum) {
+        if (e3::launch_entropy_reduce(gap_out, row_mask, rows, gap_sum_out, nullptr, stream, stop_last)
+            != hipSuccess)
             return E3_ERR_LAUNCH;
     }
     return E3_OK;
@@ -208,11 +223,14 @@ extern "C" int e3_logprob_entropy_advantages(const void* logits, int dtype, int6
     a.token_out = nullptr; a.logp_out = logp_out; a.entropy_out = entropy_out;
     a.adv_rewards = rewards; a.adv_offsets = group_offsets; a.adv_groups = num_groups;
     a.adv_ddof = ddof; a.adv_eps = eps; a.adv_out = adv_out;
+    const bool h_sum = entropy_sum_out != nullptr || entropy_count_out != nullptr;
+    hipEvent_t stop_last = nullptr;
+    if (rows > 0 && h_sum) stop_last = split_stop_event();      // measurement hook, see above
     if (e3::launch_vocab_pass(a, dtype == E3_BF16, false, workspace, workspace_bytes, stream) != hipSuccess)
         return E3_ERR_LAUNCH;
-    if (entropy_sum_out != nullptr || entropy_count_out != nullptr) {
+    if (h_sum) {
         if (e3::launch_entropy_reduce(entropy_out, row_mask, rows, entropy_sum_out, entropy_count_out,
-                                      stream) != hipSuccess)
+                                      stream, stop_last) != hipSuccess)
             return E3_ERR_LAUNCH;
     }
     return E3_OK;

@@ -50,8 +50,10 @@ int64_t static_scratch_max_rows();
 // false when V is so large that the per-workgroup tables do not fit LDS
 bool vocab_pass_fits(int64_t V);
 
+// stop_event (nullable): attached to this dispatch, holds the time the kernel ended
 hipError_t launch_entropy_reduce(const float* entropy, const uint8_t* mask, int64_t rows,
-                                 double* sum_out, int64_t* count_out, hipStream_t stream);
+                                 double* sum_out, int64_t* count_out, hipStream_t stream,
+                                 hipEvent_t stop_event = nullptr);
 
 // top-k / top-p restricted sampling of bf16 rows (one workgroup per row)
 hipError_t launch_sample_restricted(const void* logits, int64_t rows, int64_t V, int64_t row_stride,
