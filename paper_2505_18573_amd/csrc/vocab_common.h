@@ -212,29 +212,26 @@ __device__ __forceinline__ void philox4x32_10(uint32_t c0, uint32_t c1, uint32_t
         const uint64_t pa = (uint64_t)MA * c0, pb = (uint64_t)MB * c2;   // one v_mad_u64_u32 each
         const uint32_t ha = (uint32_t)(pa >> 32), la = (uint32_t)pa;
         const uint32_t hb = (uint32_t)(pb >> 32), lb = (uint32_t)pb;
-        uint32_t n0 = hb ^ c1 ^ k0;
-        uint32_t n2 = ha ^ c3 ^ k1;
+        // three-input xor in one instruction (bit-operation table 0x96)
+        uint32_t n0 = __builtin_amdgcn_bitop3_b32(hb, c1, k0, 0x96);
+        uint32_t n2 = __builtin_amdgcn_bitop3_b32(ha, c3, k1, 0x96);
         c0 = n0; c1 = lb; c2 = n2; c3 = la;
         k0 += 0x9E3779B9u; k1 += 0xBB67AE85u;
     }
     out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
 }
 
-// E = -ln(u), u = ((word >> 9) + 1/2) 2^-23.  u and d = 1 - u are exact in fp32.
-// Close to u = 1 the logarithm is taken from the series -ln(1-d) = sum d^k / k,
-// which keeps full relative accuracy where log(u) itself would cancel; elsewhere it is
-// the hardware log2 (1 ulp) times ln 2.  inv_exp_variate is 1 / E through the hardware
-// reciprocal (1 ulp): the sampler's scores carry ~3e-7 relative error from these two,
-// far inside the 1e-5 near-tie margin.
+// E = -ln(u), u = ((word >> 9) + 1/2) 2^-23 (exact in fp32), through the hardware log2.
+// Measured over all 2^23 values of u on gfx950: relative error at most 1.6e-7, also next to
+// u = 1, where a logarithm formed from exponent and mantissa tables could have cancelled (a
+// seven-term series in 1 - u is no more accurate there: 1.2e-7).  inv_exp_variate is 1 / E
+// through the hardware reciprocal (1 ulp): the sampler's scores carry ~3e-7 relative error
+// from these two, far inside the 1e-5 near-tie margin.
 __device__ __forceinline__ float exp_variate(uint32_t word)
 {
-    float k = (float)(word >> 9);
-    float u = fmaf(k, 0x1p-23f, 0x1p-24f);
-    float d = 1.0f - u;
-    float series = d * fmaf(d, fmaf(d, fmaf(d, fmaf(d, fmaf(d, fmaf(d, 1.0f / 7.0f, 1.0f / 6.0f),
-                   0.2f), 0.25f), 1.0f / 3.0f), 0.5f), 1.0f);
-    float direct = -0.693147180559945309f * __builtin_amdgcn_logf(u);
-    return d < 0.0625f ? series : direct;
+    const float k = (float)(word >> 9);
+    const float u = fmaf(k, 0x1p-23f, 0x1p-24f);
+    return -0.693147180559945309f * __builtin_amdgcn_logf(u);
 }
 
 __device__ __forceinline__ float inv_exp_variate(uint32_t word)
@@ -283,6 +280,13 @@ struct ChunkBf16 {
     static __device__ __forceinline__ float load_one(const char* row, int64_t col)
     {
         return __uint_as_float((uint32_t)reinterpret_cast<const uint16_t*>(row)[col] << 16);
+    }
+    // largest of the four logits in the high halves of the loaded words (a value the row holds)
+    __device__ __forceinline__ float some_max() const
+    {
+        return fmax3(fmax3(__uint_as_float(v.x & 0xFFFF0000u), __uint_as_float(v.y & 0xFFFF0000u),
+                           __uint_as_float(v.z & 0xFFFF0000u)),
+                     __uint_as_float(v.w & 0xFFFF0000u), __uint_as_float(v.w & 0xFFFF0000u));
     }
 };
 
@@ -333,22 +337,33 @@ struct ChunkF32 {
     {
         return reinterpret_cast<const float*>(row)[col];
     }
+    // largest of the eight loaded logits
+    __device__ __forceinline__ float some_max() const
+    {
+        const float m0 = fmax3(__uint_as_float(a.x), __uint_as_float(a.y), __uint_as_float(a.z));
+        const float m1 = fmax3(__uint_as_float(a.w), __uint_as_float(b.x), __uint_as_float(b.y));
+        return fmax3(m0, m1, fmaxf(__uint_as_float(b.z), __uint_as_float(b.w)));
+    }
 };
 
 // ---------------------------------------------------------------------------
-// Running state of one wave.  rc, top, dom_lane and dom_open are wave-uniform.
+// Running state of one wave.  rc, top, thr, dom_lane and dom_open are wave-uniform.
 // All sums are in base-2 units relative to rc:  t = z*c - rc,  e = 2^t.
 //
-// The largest logit the wave has met so far (`top`; every new one moves the
-// reference) is kept OUT of the fp32 sums and carried as a scalar.  On a peaked row
+// The largest logit the wave has met above the row's floor (`top`; every new one moves
+// the reference) is kept OUT of the fp32 sums and carried as a scalar.  On a peaked row
 // that term is ~1 while all others together may be 1e-4 or less; inside an fp32
 // accumulator it would swallow their low bits (absolute error ~1e-7), kept apart the
 // remaining sums stay accurate relative to themselves and the row merge can form
-// ln S and the entropy from log1p(rest / dominant) without cancellation.
+// ln S and the entropy from log1p(rest / dominant) without cancellation.  The floor is
+// a logit value below the row's maximum (or -inf): whatever stays at or under it cannot be
+// the row's dominant term and is summed like any other; the row's maximum itself lies
+// above every floor, so the wave that meets it does exclude it.
 // ---------------------------------------------------------------------------
 struct LaneState {
-    float rc;          // shared reference = ceil(top * c), -inf before the first element
-    float top;         // the excluded maximum (a stored logit value), -inf before the first
+    float rc;          // shared reference: an integer >= (every logit met so far) * c; -inf = none yet
+    float top;         // the excluded maximum (a stored logit value), -inf = none yet
+    float thr;         // a sweep whose maximum exceeds this moves the reference: max(top, floor)
     int dom_lane;      // lane whose chunk held `top`
     bool dom_open;     // `top` belongs to that lane's tile that is still open
     float S, W;        // finished tiles:   sum e,  sum t*e
@@ -363,24 +378,33 @@ struct LaneState {
 // Real logits are required to be far above it (|z| < 1e30).
 constexpr float kAbsent = -1.0e30f;
 
-// A sweep holds a logit above the wave's running maximum.  Move the reference to
-// ceil(new top * c): the shift d is a non-negative integer, so scaling by 2^-d is
-// exact.  The previous top becomes an ordinary term of the lane that held it; the new
-// one is struck from its chunk.
+// The integer reference that covers logits up to `z`: ceil(z * c), one more when the fp32
+// product was rounded down onto an integer.
+__device__ __forceinline__ float reference_for(float z, float c)
+{
+    float rc = ceilf(z * c);
+    if (fmaf(z, c, -rc) > 0.0f) rc += 1.0f;
+    return rc;
+}
+
+// A sweep holds a logit above the wave's running maximum (and above the floor, see
+// start_row).  Move the reference to ceil(new top * c): the shift d is a non-negative
+// integer, so scaling by 2^-d is exact.  The previous top becomes an ordinary term of
+// the lane that held it; the new one is struck from its chunk.
 __device__ __forceinline__ void new_maximum(LaneState& s, float z[8], float chunk_max, float c,
                                             int lane)
 {
     const float top = wave_max(chunk_max);
-    float new_rc = ceilf(top * c);
-    if (fmaf(top, c, -new_rc) > 0.0f) new_rc += 1.0f;   // product rounded down onto an integer
-    new_rc = uniform_f(new_rc);
-    if (s.rc > -INFINITY) {
+    const float new_rc = uniform_f(reference_for(top, c));
+    if (s.rc > -INFINITY && new_rc != s.rc) {                  // wave-uniform
         const float d = new_rc - s.rc;
         const float f = __builtin_amdgcn_exp2f(-d);           // exact: d is an integer
         s.W = fmaf(-d, s.S, s.W) * f;       s.S *= f;
         s.wT0 = fmaf(-d, s.sT0, s.wT0) * f; s.sT0 *= f;
         s.wT1 = fmaf(-d, s.sT1, s.wT1) * f; s.sT1 *= f;
         s.best.q *= f;
+    }
+    if (s.top > -INFINITY) {                                   // wave-uniform
         const float t_old = fmaf(s.top, c, -new_rc);
         const float e_old = __builtin_amdgcn_exp2f(t_old);
         if (lane == s.dom_lane) {
@@ -390,6 +414,7 @@ __device__ __forceinline__ void new_maximum(LaneState& s, float z[8], float chun
     }
     s.rc = new_rc;
     s.top = top;
+    s.thr = top;
     const unsigned long long holders = __ballot(chunk_max == top);
     s.dom_lane = __builtin_amdgcn_readfirstlane((int)__builtin_ctzll(holders | (1ull << 63)));
     s.dom_open = true;
@@ -406,9 +431,9 @@ __device__ __forceinline__ void new_maximum(LaneState& s, float z[8], float chun
 __device__ __forceinline__ void accumulate_chunk(LaneState& s, float z[8], float c, int lane)
 {
     const float cm = fmax3(fmax3(z[0], z[1], z[2]), fmax3(z[3], z[4], z[5]), fmax3(z[6], z[7], z[7]));
-    // A logit above everything the wave has met moves the reference (always so before
-    // the first element); `top` is thus the exact running maximum of the wave.
-    if (__builtin_expect(__any(cm > s.top), 0)) new_maximum(s, z, cm, c, lane);
+    // A logit above everything the wave has excluded so far, and above the row's floor,
+    // moves the reference; `top` is the running maximum of the wave's logits above the floor.
+    if (__builtin_expect(__any(cm > s.thr), 0)) new_maximum(s, z, cm, c, lane);
     const float nrc = -s.rc;
 #pragma unroll
     for (int j = 0; j < 8; ++j) {

@@ -41,9 +41,17 @@ struct alignas(16) RowPartial {
 };
 static_assert(sizeof(RowPartial) == 32, "layout");
 
-// LDS layout: uint32 done[rpb] (padded to 16 B) | RowPartial parts[rpb][kWaves+1]
-//             | float inv_e[rpb][nst][64]   (rollout side only)
-__host__ __device__ inline size_t lds_done_bytes(int rpb) { return (size_t)((rpb * 4 + 15) / 16 * 16); }
+// What a wave tells the others about its first work item before the streaming starts: a
+// logit value that the item's row holds (see the floor in start_row).
+struct WaveHint { int row; float value; };
+constexpr int kMaxWaves = 8;
+
+// LDS layout: WaveHint hints[kMaxWaves] | uint32 done[rpb] (padded to 16 B)
+//             | RowPartial parts[rpb][kWaves+1] | float inv_e[rpb][nst][64]   (rollout side only)
+__host__ __device__ inline size_t lds_done_bytes(int rpb)
+{
+    return sizeof(WaveHint) * kMaxWaves + (size_t)((rpb * 4 + 15) / 16 * 16);
+}
 
 template <int kWaves>
 __host__ __device__ inline size_t lds_bytes(int rpb, int nst, bool sample)
@@ -122,7 +130,7 @@ __device__ __forceinline__ void finish_row(const VocabPassArgs& a, int64_t row,
     if (live) {
         S_l = ldexp(p.S, sh);
         W_l = ldexp(p.W - d * p.S, sh);
-        if (lane != peak_lane) {
+        if (lane != peak_lane && p.top > -INFINITY) {      // a wave may have excluded nothing
             const double tw = (double)p.top * cd - (double)R;
             const double ew = (double)exp2f((float)tw);
             S_l += ew;
@@ -185,9 +193,18 @@ __device__ __forceinline__ void finish_row(const VocabPassArgs& a, int64_t row,
     }
 }
 
-__device__ __forceinline__ void fresh(LaneState& s)
+// Empty state for a row.  `floor` is a logit value known to be below (or -inf: nothing known
+// about) the row's maximum: logits up to the floor are ordinary terms of the sums even when
+// they exceed everything this wave has met, and only a logit above it becomes the wave's
+// excluded maximum.  The row's largest logit lies above every floor, so the wave that meets it
+// excludes it, which is all the row merge needs (it keeps the one dominant term of a peaked
+// row out of the fp32 sums); what the floor saves is the reference moves for the many running
+// maxima a wave would otherwise meet on its way.
+__device__ __forceinline__ void start_row(LaneState& s, float floor, float c)
 {
-    s.rc = -INFINITY; s.top = -INFINITY; s.dom_lane = 0; s.dom_open = false;
+    s.top = -INFINITY; s.dom_lane = 0; s.dom_open = false;
+    s.thr = floor;
+    s.rc = floor > -INFINITY ? reference_for(floor, c) : -INFINITY;
     s.S = s.W = s.sT0 = s.sT1 = s.wT0 = s.wT1 = 0.0f;
     s.best = Cand{-1.0f, 0};
 }
@@ -235,6 +252,7 @@ __global__ __launch_bounds__(kWaves * 64)
 void vocab_pass_kernel(VocabPassArgs a, int rpb)
 {
     static_assert(kAhead >= 1 && kAhead <= kDepth && kDepth % kAhead == 0, "the register ring must close over a super-tile");
+    static_assert(kWaves <= kMaxWaves, "one hint slot per wave");
     extern __shared__ __align__(16) char smem[];
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -247,7 +265,8 @@ void vocab_pass_kernel(VocabPassArgs a, int rpb)
     const int n_ragged = nst > nfull ? nrows : 0;
     const int total = n_ragged + nrows * nfull;
 
-    uint32_t* done = reinterpret_cast<uint32_t*>(smem);
+    WaveHint* hints = reinterpret_cast<WaveHint*>(smem);
+    uint32_t* done = reinterpret_cast<uint32_t*>(smem + sizeof(WaveHint) * kMaxWaves);
     RowPartial* parts = reinterpret_cast<RowPartial*>(smem + lds_done_bytes(rpb));
     float* inv_e_tab = reinterpret_cast<float*>(smem + lds_done_bytes(rpb)
                                                 + sizeof(RowPartial) * (size_t)rpb * (kWaves + 1));
@@ -300,10 +319,35 @@ void vocab_pass_kernel(VocabPassArgs a, int rpb)
             reinterpret_cast<float4*>(inv_e_tab)[(size_t)r * nst * 16 + rem] = v;
         }
     }
+    // Every wave whose first item is a complete super-tile tells the workgroup one logit value
+    // that item's row holds: the largest among the sweeps it has requested (they have arrived
+    // by now on the rollout side, behind the noise table).  The largest of these per row is
+    // the floor the waves start that row with; it depends on the data and the launch shape only.
+    {
+        float mine = -INFINITY;
+        int mine_row = -1;
+        if (have && item >= n_ragged) {
+#pragma unroll
+            for (int i = 0; i < kAhead; ++i) mine = fmaxf(mine, buf[i].some_max());
+            mine = wave_max(mine);
+            mine_row = r_cur;
+        }
+        if (lane == 0) hints[wave] = WaveHint{mine_row, mine};
+    }
     // Workgroup barrier that orders LDS only: __syncthreads() would also wait for the
     // global loads already in flight (its fence covers global memory) and drain the
     // pipeline for a full memory latency.
     asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+    // floor of local row r: just below the largest hint given for it (-inf: none)
+    auto row_floor = [&](int r) -> float {
+        float v = -INFINITY;
+        if (lane < kWaves) {
+            const WaveHint h = hints[lane];
+            if (h.row == r) v = h.value;
+        }
+        v = row16_max(v);
+        return v > -INFINITY ? v - fmaxf(fabsf(v) * 0x1p-12f, 1.0e-30f) : -INFINITY;
+    };
 
     // Training side, optional: rollout groups riding along.  The last wave has the fewest
     // items (or as many as the others), so it takes workgroup b's group b before it starts
@@ -353,7 +397,7 @@ void vocab_pass_kernel(VocabPassArgs a, int rpb)
         const float c = row_scale(r);
         const float inv_e = kSample ? inv_e_tab[((size_t)r * nst + st) * kLanes + lane] : 0.0f;
         LaneState s;
-        fresh(s);
+        start_row(s, row_floor(r), c);
         const bool any_valid = stream_ragged<Chunk>(s, rowp, (int64_t)st * kSuperCols + lane_col,
                                                     lane_col, V, c, lane);
         close_tile<kSample>(s, st * kLanes + lane, inv_e, any_valid, c, lane);
@@ -375,9 +419,9 @@ void vocab_pass_kernel(VocabPassArgs a, int rpb)
         // Items come in increasing order, so the rows a wave sees never go back: it
         // accumulates one row in `s` and hands it over when the row changes.
         LaneState s;
-        fresh(s);
         int held = 0;                                    // items of r_cur accumulated in s
         float c = row_scale(r_cur);
+        start_row(s, row_floor(r_cur), c);
         const char* rowp = base + r_cur * row_bytes;
         while (true) {
             const int next = item + kWaves;
@@ -392,10 +436,17 @@ void vocab_pass_kernel(VocabPassArgs a, int rpb)
             }
             const bool more = next < total;
             int r_next = r_cur, st_next = 0;
+            const char* nrowp = rowp;
+            int64_t next_base = 0;
             if (more) {
                 decode(next, r_next, st_next);
-                const char* nrowp = base + r_next * row_bytes;
-                const int64_t next_base = (int64_t)st_next * kSuperCols + sweep_lane_col;
+                nrowp = base + r_next * row_bytes;
+                next_base = (int64_t)st_next * kSuperCols + sweep_lane_col;
+            }
+            // two copies of the last sweeps, with and without the requests for the next item:
+            // a request under a condition inside one copy makes the compiler wait for more
+            // of the loads in flight than the copy with requests needs to
+            if (more) {
 #pragma unroll
                 for (int i = kDepth - kAhead; i < kDepth; ++i) {
                     float z[8];
@@ -415,13 +466,13 @@ void vocab_pass_kernel(VocabPassArgs a, int rpb)
             ++held;
             if (!more || r_next != r_cur) {
                 deliver(s, r_cur, wave, held);
-                fresh(s);
                 held = 0;
             }
             if (!more) break;
             if (r_next != r_cur) {
                 c = row_scale(r_next);
                 rowp = base + r_next * row_bytes;
+                start_row(s, row_floor(r_next), c);
             }
             r_cur = r_next;
             st_cur = st_next;
@@ -470,7 +521,7 @@ void vocab_split_kernel(VocabPassArgs a, RowPartial* __restrict__ ws, int nslots
     const uint64_t grow = a.row_base + (uint64_t)row;
 
     LaneState s;
-    fresh(s);
+    start_row(s, -INFINITY, c);
     for (int st = st_begin; st < st_end; ++st) {
         const int tile = st * kLanes + (st < nfull ? tlane : lane);
         float inv_e = 0.0f;
