@@ -214,7 +214,8 @@ def e3_sample_restricted(logits: torch.Tensor, tau_rows: Optional[torch.Tensor],
                          token_out: Optional[torch.Tensor] = None,
                          logp_out: Optional[torch.Tensor] = None,
                          kept_out: Optional[torch.Tensor] = None):
-    """Returns (token int32 [rows], logp fp32 [rows], kept int32 [rows]); bf16 logits only."""
+    """Returns (token int32 [rows], logp fp32 [rows], kept int32 [rows]).  bf16 rows: any
+    top_k / top_p; fp32 rows: 1 <= top_k <= 256 (E3_ERR_VALUE otherwise)."""
     dt, rows, V, stride = _logits_meta(logits)
     dev = logits.device
     if token_out is None:

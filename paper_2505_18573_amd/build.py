@@ -7,7 +7,7 @@ import subprocess
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libe3.so")
-SOURCES = ["e3_api.hip", "vocab_pass.hip", "restricted.hip", "probe.hip", "advantages.hip", "objective.hip",
+SOURCES = ["e3_api.hip", "vocab_pass.hip", "restricted.hip", "restricted_select.hip", "probe.hip", "advantages.hip", "objective.hip",
            "scheduler.cpp", "budget.cpp"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 

@@ -134,17 +134,23 @@ extern "C" int e3_sample_restricted(const void* logits, int dtype, int64_t rows,
                                     int32_t* token_out, float* logp_out, int32_t* kept_out,
                                     void* hip_stream)
 {
-    if (dtype == E3_F32) return E3_ERR_DTYPE;        // the level histogram needs 16-bit patterns
     int rc = check_logits(logits, dtype, rows, V, row_stride);
     if (rc != E3_OK) return rc;
     rc = check_tau(tau_rows, tau_scalar);
     if (rc != E3_OK) return rc;
     if (top_k < 0 || !(top_p > 0.0f) || !std::isfinite(top_p)) return E3_ERR_VALUE;
+    // a small top_k is served by selection, for both logit types; everything else needs the
+    // histogram of all bit patterns, which exists for 16-bit patterns only
+    const bool by_selection = e3::sample_select_serves(top_k);
+    if (!by_selection && dtype == E3_F32) return E3_ERR_VALUE;
     if (rows == 0) return E3_OK;
     if (token_out == nullptr) return E3_ERR_NULL;
-    hipError_t err = e3::launch_sample_restricted(logits, rows, V, row_stride, tau_rows, tau_scalar,
-                                                  top_k, top_p, seed, row_base, token_out, logp_out,
-                                                  kept_out, static_cast<hipStream_t>(hip_stream));
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    hipError_t err = by_selection
+        ? e3::launch_sample_select(logits, dtype == E3_BF16, rows, V, row_stride, tau_rows, tau_scalar,
+                                   top_k, top_p, seed, row_base, token_out, logp_out, kept_out, stream)
+        : e3::launch_sample_restricted(logits, rows, V, row_stride, tau_rows, tau_scalar, top_k, top_p,
+                                       seed, row_base, token_out, logp_out, kept_out, stream);
     return err == hipSuccess ? E3_OK : E3_ERR_LAUNCH;
 }
 

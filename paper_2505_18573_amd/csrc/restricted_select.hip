@@ -1,0 +1,690 @@
+// Restricted (top-k, optionally followed by top-p) sampling for small k, bf16 and fp32
+// rows, for gfx950.
+//
+// Paper: arXiv 2505.18573 samples its rollouts unrestricted at temperature tau (Section
+// 5.1); the truncations are the library's own definition, stated in include/e3.h on value
+// LEVELS (the columns that store one bit pattern).  restricted.hip implements it for bf16
+// rows through a histogram of all 65,536 patterns; that costs one LDS atomic per column and
+// cannot hold the 2^32 patterns of fp32.  For top_k <= 256 the kept set is tiny, and this
+// file finds it by selection instead:
+//   1. one streaming read of the row leaves the maximum of every chunk of columns in LDS
+//      (plain vector maxima: about two instructions per column, no atomics) and every
+//      thread's own maximum in a register;
+//   2. theta = the k-th largest of the 1024 thread maxima is a lower bound of the k-th
+//      largest column (k different threads hold a column at or above it), and a tight one:
+//      only the few chunks whose maximum reaches theta can hold kept columns;
+//   3. the columns at or above theta are read again from those chunks and listed in LDS; an
+//      exact radix select over them gives kappa, the value of the cut level, with the number
+//      of columns above it (fewer than k) and on it;
+//   4. the columns above kappa are listed, sorted by (value, column), grouped into levels
+//      with their fp64 masses, cut by top-p, raced and the winning level's pos-th column
+//      taken, exactly as the definition says; the cut level takes part with its count.
+// Every count is exact and every mass fp64, as in restricted.hip; a row with enormous
+// plateaus of equal values is slow (its chunks all qualify) but takes the same path.
+#include "vocab_common.h"
+#include "vocab_pass.h"
+
+namespace e3 {
+namespace {
+
+constexpr int kSThreads = 1024;
+constexpr int kSWaves = kSThreads / 64;
+constexpr int kSMaxK = 256;             // top_k served here; the gt-list holds at most kSMaxK - 1 columns
+constexpr int kSEqCap = 64;             // columns of the cut level listed for a direct pick
+constexpr int kSListCap = 2048;         // candidates (columns at or above theta) listed in LDS
+constexpr uint32_t kKeyPosZero = 0x80000000u, kKeyNegZero = 0x7FFFFFFFu;
+
+// Monotone map of a binary32 pattern to an unsigned key (value order, -0 just below +0);
+// patterns that are not finite numbers get key 0, below every level.
+__device__ __forceinline__ uint32_t key_of_f32(uint32_t bits)
+{
+    if ((bits & 0x7F800000u) == 0x7F800000u) return 0u;
+    return (bits & 0x80000000u) ? ~bits : (bits | 0x80000000u);
+}
+__device__ __forceinline__ uint32_t f32_of_key(uint32_t key)
+{
+    return (key & 0x80000000u) ? (key & 0x7FFFFFFFu) : ~key;
+}
+
+// Element access for the two logit types.  A vector is 16 bytes.  Keys are 32-bit in
+// registers; bf16 rows store their chunk maxima as the upper 16 bits (the lower 16 of a bf16
+// value's key are all ones or all zeros and can be rebuilt).
+struct SelBf16 {
+    typedef uint16_t Stored;
+    static constexpr int kElems = 8;
+    static constexpr int kChunksPerThreadMax = 20;   // 40 KiB of chunk maxima
+    static constexpr int kKeyBits = 16;              // significant key bits, from the top
+    static __device__ __forceinline__ uint32_t elem_bits(const u32x4& v, int j)   // as binary32
+    {
+        const uint32_t w = j < 2 ? v.x : j < 4 ? v.y : j < 6 ? v.z : v.w;
+        return (j & 1) ? (w & 0xFFFF0000u) : (w << 16);
+    }
+    static __device__ __forceinline__ Stored pack(uint32_t key) { return (Stored)(key >> 16); }
+    // the largest key with these upper bits: never below the key that was packed
+    static __device__ __forceinline__ uint32_t unpack_upper(Stored s) { return ((uint32_t)s << 16) | 0xFFFFu; }
+    static __device__ __forceinline__ uint32_t pattern_of_bits(uint32_t bits) { return bits >> 16; }
+    static __device__ __forceinline__ float vec_max(const u32x4& v)
+    {
+        return fmax3(fmax3(__uint_as_float(v.x << 16), __uint_as_float(v.x & 0xFFFF0000u), __uint_as_float(v.y << 16)),
+                     fmax3(__uint_as_float(v.y & 0xFFFF0000u), __uint_as_float(v.z << 16), __uint_as_float(v.z & 0xFFFF0000u)),
+                     fmaxf(__uint_as_float(v.w << 16), __uint_as_float(v.w & 0xFFFF0000u)));
+    }
+};
+struct SelF32 {
+    typedef uint32_t Stored;
+    static constexpr int kElems = 4;
+    static constexpr int kChunksPerThreadMax = 10;   // 40 KiB of chunk maxima
+    static constexpr int kKeyBits = 32;
+    static __device__ __forceinline__ uint32_t elem_bits(const u32x4& v, int j)
+    {
+        return j == 0 ? v.x : j == 1 ? v.y : j == 2 ? v.z : v.w;
+    }
+    static __device__ __forceinline__ Stored pack(uint32_t key) { return key; }
+    static __device__ __forceinline__ uint32_t unpack_upper(Stored s) { return s; }
+    static __device__ __forceinline__ uint32_t pattern_of_bits(uint32_t bits) { return bits; }
+    static __device__ __forceinline__ float vec_max(const u32x4& v)
+    {
+        return fmax3(fmax3(__uint_as_float(v.x), __uint_as_float(v.y), __uint_as_float(v.z)),
+                     __uint_as_float(v.w), __uint_as_float(v.w));
+    }
+};
+
+struct SelShared {
+    uint32_t hist[256];
+    uint32_t prefix, k_rem, n_eq_last;      // radix select state
+    uint32_t n_total;                        // candidates seen by the first pass
+    int gt_n, eq_n, list_n;                  // list fills
+    int rank[kSMaxK];
+    uint32_t gt_key[kSMaxK];                 // unsorted, then sorted by (key desc, col asc)
+    int32_t gt_col[kSMaxK];
+    uint32_t st_key[kSMaxK];
+    int32_t st_col[kSMaxK];
+    double st_M[kSMaxK];                     // inclusive prefix mass in sorted order
+    int32_t eq_col[kSEqCap];
+    int cut_index;                           // last kept entry of the sorted list (-1: none), or kSMaxK: cut level kept
+    float wave_q[kSWaves];
+    int wave_lvl[kSWaves];
+    int wave_hits[kSWaves];
+    int token;
+    uint32_t tmax_wave[kSWaves];
+};
+
+// Largest unsigned value of the wave, returned wave-uniform (DPP butterfly as in wave_best).
+template <int kCtrl, int kRowMask = 0xF>
+__device__ __forceinline__ uint32_t umax_step(uint32_t v)
+{
+    const uint32_t o = (uint32_t)dpp_i<kCtrl, kRowMask>((int)v, (int)v);   // rows masked off see themselves
+    return o > v ? o : v;
+}
+__device__ __forceinline__ uint32_t wave_max_u32(uint32_t v)
+{
+    v = umax_step<kDppXor1>(v);
+    v = umax_step<kDppXor2>(v);
+    v = umax_step<kDppHalfMirror>(v);
+    v = umax_step<kDppMirror>(v);
+    v = umax_step<kDppBcast15, 0xA>(v);
+    v = umax_step<kDppBcast31, 0xC>(v);
+    return (uint32_t)__builtin_amdgcn_readlane((int)v, 63);
+}
+
+// One 8-bit pass of a radix select for the k-th largest: every thread has added its keys
+// that match `prefix` above `shift + 8` to hist; wave 0 finds the digit that holds rank k_rem.
+__device__ __forceinline__ void select_digit(SelShared& sh, int tid)
+{
+    if (tid < 64) {
+        // lane l owns bins 255 - 4l .. 252 - 4l (descending)
+        uint32_t c[4], sum = 0;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) { c[j] = sh.hist[255 - 4 * tid - j]; sum += c[j]; }
+        uint32_t inc = sum;
+#pragma unroll
+        for (int d = 1; d < 64; d <<= 1) {
+            const uint32_t o = __shfl_up(inc, d, 64);
+            if (tid >= d) inc += o;
+        }
+        uint32_t before = inc - sum;                       // counts in higher bins
+        const uint32_t k = sh.k_rem;
+        if (before < k && k <= inc) {                       // exactly one lane
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                if (before < k && k <= before + c[j]) {
+                    sh.prefix = (sh.prefix << 8) | (uint32_t)(255 - 4 * tid - j);
+                    sh.k_rem = k - before;
+                    sh.n_eq_last = c[j];
+                    before = 0xFFFFFFFFu;                   // done
+                } else if (before != 0xFFFFFFFFu) {
+                    before += c[j];
+                }
+            }
+        }
+    }
+}
+
+struct SelArgs {
+    const void* logits;
+    int64_t rows, V, row_stride;
+    const float* tau_rows;
+    float tau_scalar;
+    int32_t top_k;
+    float top_p;
+    uint64_t seed, row_base;
+    int32_t* token_out;
+    float* logp_out;
+    int32_t* kept_out;
+    int group;            // vectors per chunk
+    int chunks;           // chunks per thread
+};
+
+// Two workgroups of sixteen waves per compute unit need eight waves per SIMD: at most 64
+// vector and 96 scalar registers per wave (gfx9 SIMDs hold 800 scalar registers).
+template <typename T>
+__global__ __launch_bounds__(kSThreads) __attribute__((amdgpu_waves_per_eu(8, 8)))
+void sample_select_kernel(SelArgs a)
+{
+    extern __shared__ __align__(16) unsigned char dyn[];
+    typename T::Stored* cmax = reinterpret_cast<typename T::Stored*>(dyn);
+    __shared__ SelShared sh;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int64_t row = blockIdx.x;
+    const int64_t V = a.V;
+    const int esz = 16 / T::kElems;
+    const char* rowp = static_cast<const char*>(a.logits) + row * a.row_stride * esz;
+    const u32x4* rv = reinterpret_cast<const u32x4*>(rowp);
+    const int64_t nvec = (V + T::kElems - 1) / T::kElems;     // the last one may reach past V (inside the row pitch)
+    const int G = a.group, CPT = a.chunks;
+    const float tau = a.tau_rows ? a.tau_rows[row] : a.tau_scalar;
+    const double inv_tau = 1.0 / (double)tau;
+    const float c = kLog2eF / tau;
+    const uint64_t grow = a.row_base + (uint64_t)row;
+
+    // ---- 1. chunk maxima ------------------------------------------------------------------
+    // chunk j of thread t = vectors t + 1024 (j G + g), g < G.  Maxima are taken as floats
+    // (NaN operands drop out of v_max3); +inf is dealt with below; a maximum of zero is
+    // recorded as +0, whichever zero it was.
+    auto vec_key_max = [&](int64_t v, const u32x4& x) -> uint32_t {
+        float m = T::vec_max(x);
+        if (v == nvec - 1 && nvec * T::kElems != V) {           // columns past V do not count
+            m = -INFINITY;
+            for (int j = 0; j < T::kElems; ++j)
+                if (v * T::kElems + j < V) m = fmaxf(m, __uint_as_float(T::elem_bits(x, j)));
+        }
+        uint32_t key = m == 0.0f ? kKeyPosZero : key_of_f32(__float_as_uint(m));
+        if (m == INFINITY) {                                      // skip the non-finite ones by hand
+            key = 0u;
+            for (int j = 0; j < T::kElems; ++j)
+                if (v * T::kElems + j < V) {
+                    const uint32_t kj = key_of_f32(T::elem_bits(x, j));
+                    key = kj > key ? kj : key;
+                }
+        }
+        return key;
+    };
+    // Vector slots s = j G + g of this thread, four requests in flight at a time.
+    uint32_t tmax = 0u;
+    {
+        const int nslots = CPT * G;
+        uint32_t m = 0u;                                          // maximum of the chunk being filled
+        for (int s0 = 0; s0 < nslots; s0 += 4) {
+            u32x4 x[4];
+            int64_t vv[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                vv[u] = (int64_t)tid + (int64_t)kSThreads * (s0 + u);
+                x[u] = (s0 + u < nslots && vv[u] < nvec) ? rv[vv[u]] : u32x4{0u, 0u, 0u, 0u};
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int sl = s0 + u;
+                if (sl < nslots) {
+                    if (vv[u] < nvec) { const uint32_t k1 = vec_key_max(vv[u], x[u]); m = k1 > m ? k1 : m; }
+                    if ((sl + 1) % G == 0) {                      // last vector of chunk sl / G
+                        cmax[(size_t)(sl / G) * kSThreads + tid] = T::pack(m);
+                        tmax = m > tmax ? m : tmax;
+                        m = 0u;
+                    }
+                }
+            }
+        }
+    }
+
+    // ---- 2. theta: the k-th largest thread maximum ---------------------------------------------
+    const unsigned long long have_w = __ballot(tmax != 0u);
+    if (lane == 0) sh.wave_hits[wave] = __popcll(have_w);
+    if (tid == 0) { sh.gt_n = 0; sh.eq_n = 0; sh.token = 0; }
+    __syncthreads();
+    int n_threads_with = 0;
+    for (int w = 0; w < kSWaves; ++w) n_threads_with += sh.wave_hits[w];
+    __syncthreads();
+    if (n_threads_with == 0) {                                    // no finite logit in the row
+        if (tid == 0) {
+            a.token_out[row] = 0;
+            if (a.kept_out) a.kept_out[row] = 0;
+            if (a.logp_out) a.logp_out[row] = __builtin_nanf("");
+        }
+        return;
+    }
+    // Each wave takes the m-th largest of its lanes' maxima, m = ceil(k / 16), by striking the
+    // largest m - 1 times; the smallest of the sixteen results has 16 m >= k threads at or above
+    // it.  No atomics, one barrier.  (The exact k-th largest of the 1024 would be a little
+    // tighter; it costs two to four histogram passes with their barriers.)
+    const int k_req = a.top_k < kSMaxK ? a.top_k : kSMaxK;
+    uint32_t theta;
+    {
+        const int m_th = (k_req + kSWaves - 1) / kSWaves;
+        uint32_t rest = tmax, wm = 0u;
+        for (int it = 0; it < m_th; ++it) {
+            wm = wave_max_u32(rest);
+            if (it + 1 < m_th) {
+                const unsigned long long holders = __ballot(rest == wm);
+                if (lane == (int)__builtin_ctzll(holders | (1ull << 63))) rest = 0u;
+            }
+        }
+        if (lane == 0) sh.tmax_wave[wave] = wm;
+        __syncthreads();
+        theta = 0xFFFFFFFFu;
+        for (int w = 0; w < kSWaves; ++w) theta = sh.tmax_wave[w] < theta ? sh.tmax_wave[w] : theta;
+        if (theta == 0u) theta = 1u;                                // a wave with fewer than m finite maxima: every finite value
+        // a zero maximum was recorded as +0 whichever zero it was: let -0 in as well
+        if (theta == kKeyPosZero) theta = kKeyNegZero;
+    }
+
+    // ---- 3. the candidates: every finite column whose key reaches theta ----------------------------
+    // They sit in the chunks whose maximum reaches theta.  Usually there are a few hundred: they
+    // are read once more and listed in LDS (key, column), and everything below works on the list.
+    // A row with huge plateaus of equal values overflows the list; it is then read from memory
+    // in every pass instead (slow, same results).
+    uint32_t* lkey = reinterpret_cast<uint32_t*>(dyn + (size_t)CPT * kSThreads * sizeof(typename T::Stored));
+    int32_t* lcol = reinterpret_cast<int32_t*>(lkey + kSListCap);
+    auto stream_candidates = [&](auto&& f) {
+        for (int j = 0; j < CPT; ++j) {
+            if (T::unpack_upper(cmax[(size_t)j * kSThreads + tid]) < theta) continue;
+            for (int g = 0; g < G; ++g) {
+                const int64_t v = (int64_t)tid + (int64_t)kSThreads * ((int64_t)j * G + g);
+                if (v >= nvec) break;
+                const u32x4 x = rv[v];
+#pragma unroll
+                for (int e = 0; e < T::kElems; ++e) {
+                    const int64_t col = v * T::kElems + e;
+                    const uint32_t key = key_of_f32(T::elem_bits(x, e));
+                    if (col < V && key >= theta) f(key, (int32_t)col);
+                }
+            }
+        }
+    };
+    // one slot per true flag, one LDS atomic per wave instruction
+    auto wave_slot = [&](bool flag, int* counter) -> int {
+        const unsigned long long m = __ballot(flag);
+        if (m == 0ull) return -1;
+        int base = 0;
+        const int leader = (int)__builtin_ctzll(m);
+        if (lane == leader) base = atomicAdd(counter, __popcll(m));
+        base = __shfl(base, leader, 64);
+        return base + __popcll(m & ((1ull << lane) - 1ull));
+    };
+    if (tid == 0) sh.list_n = 0;
+    __syncthreads();
+    {
+        // qualifying vectors of this thread, requested four at a time
+        int64_t vq[4];
+        int nq = 0;
+        auto flush = [&]() {
+            u32x4 x[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) x[u] = u < nq ? rv[vq[u]] : u32x4{0u, 0u, 0u, 0u};
+            // count my candidates, reserve a run of slots for the wave, write mine in order
+            uint32_t ok_mask = 0u;
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+#pragma unroll
+                for (int e = 0; e < T::kElems; ++e) {
+                    const int64_t col = (u < nq ? vq[u] : 0) * T::kElems + e;
+                    const uint32_t key = key_of_f32(T::elem_bits(x[u], e));
+                    ok_mask |= (uint32_t)(u < nq && col < V && key >= theta) << (u * T::kElems + e);
+                }
+            }
+            const int mine = __popc(ok_mask);
+            int inc = mine;
+#pragma unroll
+            for (int d = 1; d < 64; d <<= 1) {
+                const int o = __shfl_up(inc, d, 64);
+                if (lane >= d) inc += o;
+            }
+            const int wave_total = __shfl(inc, 63, 64);
+            int base = 0;
+            if (lane == 63 && wave_total > 0) base = atomicAdd(&sh.list_n, wave_total);
+            base = __shfl(base, 63, 64);
+            int slot = base + inc - mine;
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+#pragma unroll
+                for (int e = 0; e < T::kElems; ++e) {
+                    if (ok_mask & (1u << (u * T::kElems + e))) {
+                        if (slot < kSListCap) {
+                            lkey[slot] = key_of_f32(T::elem_bits(x[u], e));
+                            lcol[slot] = (int32_t)(vq[u] * T::kElems + e);
+                        }
+                        ++slot;
+                    }
+                }
+            }
+            nq = 0;
+        };
+        // all lanes of a wave flush together (the slot reservation is a wave-wide operation)
+        for (int sl = 0; sl < CPT * G; ++sl) {
+            const int64_t v = (int64_t)tid + (int64_t)kSThreads * sl;
+            const bool q = v < nvec && T::unpack_upper(cmax[(size_t)(sl / G) * kSThreads + tid]) >= theta;
+            if (q) vq[nq++] = v;
+            if (__any(nq == 4)) flush();
+        }
+        if (__any(nq > 0)) flush();
+    }
+    __syncthreads();
+    const int n_list = sh.list_n;
+    const bool listed = n_list <= kSListCap;
+    auto for_each_candidate = [&](auto&& f) {
+        if (listed) {
+            for (int e = tid; e < n_list; e += kSThreads) f(lkey[e], lcol[e]);
+        } else {
+            stream_candidates(f);
+        }
+    };
+
+    // ---- 4. kappa: the k-th largest column (exact), by radix select over the candidates ---------
+    if (tid == 0) { sh.prefix = 0u; sh.k_rem = 0u; sh.n_total = 0u; }
+    uint32_t k_col = (uint32_t)k_req;
+    for (int pass = 0; pass < T::kKeyBits / 8; ++pass) {
+        const int shift = 24 - 8 * pass;
+        if (tid < 256) sh.hist[tid] = 0u;
+        __syncthreads();
+        const uint32_t prefix = sh.prefix;
+        for_each_candidate([&](uint32_t key, int32_t) {
+            if (pass == 0 || (key >> (shift + 8)) == prefix) atomicAdd(&sh.hist[(key >> shift) & 255u], 1u);
+        });
+        __syncthreads();
+        if (pass == 0) {
+            // number of candidates; fewer than k finite columns in the row: the cut is the lowest level
+            if (tid < 64) {
+                uint32_t t = sh.hist[tid] + sh.hist[tid + 64] + sh.hist[tid + 128] + sh.hist[tid + 192];
+#pragma unroll
+                for (int d = 32; d > 0; d >>= 1) t += __shfl_xor(t, d, 64);
+                if (tid == 0) { sh.n_total = t; sh.k_rem = t < k_col ? t : k_col; }
+            }
+            __syncthreads();
+        }
+        select_digit(sh, tid);
+        __syncthreads();
+    }
+    const uint32_t kappa = T::kKeyBits == 32 ? sh.prefix
+                         : ((sh.prefix << 16) | ((sh.prefix & 0x8000u) ? 0u : 0xFFFFu));   // rebuild a bf16 value's key
+    const int n_cut = (int)sh.n_eq_last;                          // columns on the cut level
+    const uint32_t k_eff = sh.n_total < k_col ? sh.n_total : k_col;
+    const int count_gt = (int)(k_eff - sh.k_rem);                 // columns above it (< k)
+    __syncthreads();
+
+    // ---- 5. the columns above kappa, and those on it when they are few -------------------------------
+    if (listed) {
+        for (int e0 = 0; e0 < n_list; e0 += kSThreads) {          // whole waves: wave_slot is wave-wide
+            const int e = e0 + tid;
+            const uint32_t key = e < n_list ? lkey[e] : 0u;
+            const int32_t col = e < n_list ? lcol[e] : 0;
+            const int sg = wave_slot(key > kappa, &sh.gt_n);
+            if (key > kappa && sg < kSMaxK) { sh.gt_key[sg] = key; sh.gt_col[sg] = col; }
+            const bool eq = key == kappa && n_cut <= kSEqCap;
+            const int se = wave_slot(eq, &sh.eq_n);
+            if (eq && se < kSEqCap) sh.eq_col[se] = col;
+        }
+    } else {
+        stream_candidates([&](uint32_t key, int32_t col) {
+            if (key > kappa) {
+                const int slot = atomicAdd(&sh.gt_n, 1);
+                if (slot < kSMaxK) { sh.gt_key[slot] = key; sh.gt_col[slot] = col; }
+            } else if (key == kappa && n_cut <= kSEqCap) {
+                const int slot = atomicAdd(&sh.eq_n, 1);
+                if (slot < kSEqCap) sh.eq_col[slot] = col;
+            }
+        });
+    }
+    __syncthreads();
+    const int n = count_gt;                                        // == sh.gt_n
+    // sort by (key descending, column ascending): rank by counting, the n x n comparisons spread
+    // over all threads (entry i = tid mod 256 against a quarter of the others each)
+    if (tid < kSMaxK) sh.rank[tid] = 0;
+    __syncthreads();
+    {
+        const int i = tid & (kSMaxK - 1), quarter = tid / kSMaxK;
+        if (i < n) {
+            const uint32_t mk = sh.gt_key[i];
+            const int32_t mc = sh.gt_col[i];
+            const int e_begin = quarter * ((n + 3) / 4);
+            const int e_end = e_begin + (n + 3) / 4 < n ? e_begin + (n + 3) / 4 : n;
+            int r = 0;
+#pragma unroll 8
+            for (int e = e_begin; e < e_end; ++e) {
+                const uint32_t ok = sh.gt_key[e];
+                const int32_t oc = sh.gt_col[e];
+                r += (ok > mk) || (ok == mk && oc < mc);
+            }
+            if (r != 0) atomicAdd(&sh.rank[i], r);
+        }
+    }
+    __syncthreads();
+    if (tid < n) {
+        const int r = sh.rank[tid];
+        sh.st_key[r] = sh.gt_key[tid];
+        sh.st_col[r] = sh.gt_col[tid];
+    }
+    __syncthreads();
+
+    // ---- 6. masses in rank order (fp64), cuts -----------------------------------------------------
+    const uint32_t key1 = n > 0 ? sh.st_key[0] : kappa;           // the row's highest level
+    const double z1 = (double)__uint_as_float(f32_of_key(key1));
+    const double z_cut = (double)__uint_as_float(f32_of_key(kappa));
+    if (tid < n) sh.st_M[tid] = exp(((double)__uint_as_float(f32_of_key(sh.st_key[tid])) - z1) * inv_tau);
+    __syncthreads();
+    if (tid < 64) {
+        // wave 0: lane l holds sorted entries 4l .. 4l+3; inclusive prefix sums in rank order
+        double w[4], loc = 0.0;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int i = 4 * tid + j;
+            w[j] = i < n ? sh.st_M[i] : 0.0;
+            loc += w[j];
+        }
+        double inc = loc;
+#pragma unroll
+        for (int d = 1; d < 64; d <<= 1) {
+            const double o = __shfl_up(inc, d, 64);
+            if (tid >= d) inc += o;
+        }
+        double run = inc - loc;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int i = 4 * tid + j;
+            run += w[j];
+            if (i < n) sh.st_M[i] = run;
+        }
+    }
+    __syncthreads();
+    const double M_gt = n > 0 ? sh.st_M[n - 1] : 0.0;
+    const double w_cut = exp((z_cut - z1) * inv_tau);
+    const double M_k = M_gt + (double)n_cut * w_cut;              // mass of the top-k set
+    // top-p on the renormalised top-k set: first level end whose cumulative mass reaches T
+    if (tid == 0) sh.cut_index = kSMaxK;                           // default: everything down to the cut level
+    __syncthreads();
+    if (a.top_p < 1.0f) {
+        const double Tm = (double)a.top_p * M_k;
+        if (tid < n) {
+            const bool level_end = tid == n - 1 || sh.st_key[tid + 1] != sh.st_key[tid];
+            if (level_end && sh.st_M[tid] >= Tm) atomicMin(&sh.cut_index, tid);
+        }
+        __syncthreads();
+    }
+    const int cut_index = sh.cut_index;
+    const bool cut_level_kept = cut_index == kSMaxK;
+    const int kept_sorted = cut_level_kept ? n : cut_index + 1;    // sorted entries kept
+    const int kept_C = cut_level_kept ? n + n_cut : kept_sorted;
+    const double kept_M = cut_level_kept ? M_k : sh.st_M[cut_index];
+
+    // ---- 7. race of the kept levels ------------------------------------------------------------------
+    // score n_j w_j / E_j, E_j from Philox stream 3 at index = the level's stored pattern; fp32
+    // scores as in the unrestricted sampler; ties go to the higher level = lower sorted index.
+    const float z1f = __uint_as_float(f32_of_key(key1));
+    auto level_score = [&](uint32_t key, int cnt) -> float {
+        const uint32_t bits = f32_of_key(key);
+        const uint32_t pat = T::pattern_of_bits(bits);
+        uint32_t w4[4];
+        philox4x32_10(pat >> 2, (uint32_t)grow, (uint32_t)(grow >> 32), 3u,
+                      (uint32_t)a.seed, (uint32_t)(a.seed >> 32), w4);
+        const int sel = pat & 3;
+        const uint32_t word = sel == 0 ? w4[0] : sel == 1 ? w4[1] : sel == 2 ? w4[2] : w4[3];
+        return (float)cnt * __builtin_amdgcn_exp2f((__uint_as_float(bits) - z1f) * c) * inv_exp_variate(word);
+    };
+    float my_q = -1.0f;
+    int my_lvl = 0x7FFFFFFF;                                       // sorted index of the level's first entry; kSMaxK = cut level
+    if (tid < kept_sorted) {
+        const bool level_start = tid == 0 || sh.st_key[tid - 1] != sh.st_key[tid];
+        if (level_start) {
+            int cnt = 1;
+            while (tid + cnt < n && sh.st_key[tid + cnt] == sh.st_key[tid]) ++cnt;
+            my_q = level_score(sh.st_key[tid], cnt);
+            my_lvl = tid;
+        }
+    } else if (tid == kSThreads - 1 && cut_level_kept) {
+        my_q = level_score(kappa, n_cut);
+        my_lvl = kSMaxK;
+    }
+#pragma unroll
+    for (int d = 32; d > 0; d >>= 1) {
+        const float oq = __shfl_xor(my_q, d, 64);
+        const int ol = __shfl_xor(my_lvl, d, 64);
+        if (oq > my_q || (oq == my_q && ol < my_lvl)) { my_q = oq; my_lvl = ol; }
+    }
+    if (lane == 0) { sh.wave_q[wave] = my_q; sh.wave_lvl[wave] = my_lvl; }
+    __syncthreads();
+    float best_q = -1.0f;
+    int best_lvl = 0x7FFFFFFF;
+    for (int w = 0; w < kSWaves; ++w) {
+        const float q = sh.wave_q[w];
+        const int l = sh.wave_lvl[w];
+        if (q > best_q || (q == best_q && l < best_lvl)) { best_q = q; best_lvl = l; }
+    }
+
+    // ---- 8. the column inside the winning level ---------------------------------------------------------
+    uint32_t w4[4];
+    philox4x32_10(0u, (uint32_t)grow, (uint32_t)(grow >> 32), 4u, (uint32_t)a.seed, (uint32_t)(a.seed >> 32), w4);
+    const uint64_t k23 = (uint64_t)(w4[0] >> 9);
+    int tok = 0;
+    uint32_t tok_key = key1;
+    if (best_q >= 0.0f && best_lvl < kSMaxK) {
+        int cnt = 1;
+        while (best_lvl + cnt < n && sh.st_key[best_lvl + cnt] == sh.st_key[best_lvl]) ++cnt;
+        const int pos = (int)(((2u * k23 + 1u) * (uint64_t)cnt) >> 24);
+        tok = sh.st_col[best_lvl + pos];                           // a level's entries are in column order
+        tok_key = sh.st_key[best_lvl];
+    } else if (best_q >= 0.0f) {
+        const int pos = (int)(((2u * k23 + 1u) * (uint64_t)n_cut) >> 24);
+        tok_key = kappa;
+        if (n_cut <= kSEqCap) {
+            // the pos-th smallest of the listed columns
+            if (tid < n_cut) {
+                const int32_t mc = sh.eq_col[tid];
+                int rank = 0;
+                for (int e = 0; e < n_cut; ++e) rank += sh.eq_col[e] < mc;
+                if (rank == pos) sh.token = mc;
+            }
+            __syncthreads();
+            tok = sh.token;
+        } else {
+            // a plateau: count the level's columns in column order; waves take contiguous runs of vectors
+            const int64_t per_wave = (nvec + kSWaves - 1) / kSWaves;
+            const int64_t v_begin = (int64_t)wave * per_wave < nvec ? (int64_t)wave * per_wave : nvec;
+            const int64_t v_end = v_begin + per_wave < nvec ? v_begin + per_wave : nvec;
+            auto mask_of = [&](int64_t v) -> uint32_t {
+                const u32x4 x = rv[v];
+                uint32_t m = 0;
+#pragma unroll
+                for (int e = 0; e < T::kElems; ++e)
+                    m |= (uint32_t)(v * T::kElems + e < V && key_of_f32(T::elem_bits(x, e)) == kappa) << e;
+                return m;
+            };
+            int hits = 0;
+            for (int64_t v = v_begin + lane; v < v_end; v += 64) hits += __popc(mask_of(v));
+#pragma unroll
+            for (int d = 32; d > 0; d >>= 1) hits += __shfl_xor(hits, d, 64);
+            if (lane == 0) sh.wave_hits[wave] = hits;
+            __syncthreads();
+            int before = 0;
+            for (int w = 0; w < wave; ++w) before += sh.wave_hits[w];
+            if (pos >= before && pos < before + hits) {            // uniform per wave: my run holds it
+                int rem = pos - before;
+                for (int64_t v0 = v_begin; v0 < v_end; v0 += 64) {
+                    const int64_t v = v0 + lane;
+                    const uint32_t m = v < v_end ? mask_of(v) : 0u;
+                    const int cc = __popc(m);
+                    int inc = cc;
+#pragma unroll
+                    for (int d = 1; d < 64; d <<= 1) {
+                        const int o = __shfl_up(inc, d, 64);
+                        if (lane >= d) inc += o;
+                    }
+                    const int sweep_total = __shfl(inc, 63, 64);
+                    if (rem < sweep_total) {
+                        if (rem >= inc - cc && rem < inc) {        // exactly one lane
+                            int skip = rem - (inc - cc);
+                            uint32_t mm = m;
+                            while (skip-- > 0) mm &= mm - 1;       // drop the lowest set bits
+                            sh.token = (int)(v * T::kElems + (__ffs(mm) - 1));
+                        }
+                        break;
+                    }
+                    rem -= sweep_total;
+                }
+            }
+            __syncthreads();
+            tok = sh.token;
+        }
+    }
+    if (tid == 0) {
+        if (tok < 0 || tok >= V) tok = 0;
+        a.token_out[row] = tok;
+        if (a.kept_out) a.kept_out[row] = kept_C;
+        if (a.logp_out)
+            a.logp_out[row] = best_q >= 0.0f
+                ? (float)(((double)__uint_as_float(f32_of_key(tok_key)) - z1) * inv_tau - log(kept_M))
+                : __builtin_nanf("");
+    }
+}
+
+}  // namespace
+
+bool sample_select_serves(int32_t top_k) { return top_k >= 1 && top_k <= kSMaxK; }
+
+hipError_t launch_sample_select(const void* logits, bool is_bf16, int64_t rows, int64_t V, int64_t row_stride,
+                                const float* tau_rows, float tau_scalar, int32_t top_k, float top_p,
+                                uint64_t seed, uint64_t row_base, int32_t* token_out,
+                                float* logp_out, int32_t* kept_out, hipStream_t stream)
+{
+    if (rows == 0) return hipSuccess;
+    SelArgs a;
+    a.logits = logits; a.rows = rows; a.V = V; a.row_stride = row_stride;
+    a.tau_rows = tau_rows; a.tau_scalar = tau_scalar;
+    a.top_k = top_k; a.top_p = top_p;
+    a.seed = seed; a.row_base = row_base;
+    a.token_out = token_out; a.logp_out = logp_out; a.kept_out = kept_out;
+    const int elems = is_bf16 ? SelBf16::kElems : SelF32::kElems;
+    const int cpt_max = is_bf16 ? SelBf16::kChunksPerThreadMax : SelF32::kChunksPerThreadMax;
+    const int64_t nvec = (V + elems - 1) / elems;
+    const int64_t vpt = (nvec + kSThreads - 1) / kSThreads;           // vectors per thread
+    a.group = (int)((vpt + cpt_max - 1) / cpt_max);
+    if (a.group < 1) a.group = 1;
+    a.chunks = (int)((vpt + a.group - 1) / a.group);
+    const size_t lds = (size_t)a.chunks * kSThreads * (is_bf16 ? sizeof(SelBf16::Stored) : sizeof(SelF32::Stored))
+                     + (size_t)kSListCap * 8;
+    if (is_bf16)
+        hipLaunchKernelGGL(sample_select_kernel<SelBf16>, dim3((unsigned)rows), dim3(kSThreads), lds, stream, a);
+    else
+        hipLaunchKernelGGL(sample_select_kernel<SelF32>, dim3((unsigned)rows), dim3(kSThreads), lds, stream, a);
+    return hipGetLastError();
+}
+
+}  // namespace e3

@@ -61,6 +61,14 @@ hipError_t launch_sample_restricted(const void* logits, int64_t rows, int64_t V,
                                     uint64_t seed, uint64_t row_base, int32_t* token_out,
                                     float* logp_out, int32_t* kept_out, hipStream_t stream);
 
+// top-k (<= 256, see sample_select_serves) / top-p restricted sampling by selection, bf16 and
+// fp32 rows (one workgroup per row)
+bool sample_select_serves(int32_t top_k);
+hipError_t launch_sample_select(const void* logits, bool is_bf16, int64_t rows, int64_t V, int64_t row_stride,
+                                const float* tau_rows, float tau_scalar, int32_t top_k, float top_p,
+                                uint64_t seed, uint64_t row_base, int32_t* token_out,
+                                float* logp_out, int32_t* kept_out, hipStream_t stream);
+
 // read-bandwidth probe: kReadProbeBlocks xor checksums of `bytes` (multiple of 16) bytes
 constexpr int kReadProbeBlocks = 2048;
 hipError_t launch_read_probe(const void* buf, int64_t bytes, uint32_t* sums, hipStream_t stream);

@@ -155,7 +155,9 @@ def test_argument_checks_need_no_gpu():
     L = e3.lib()
     call = lambda dtype=1, k=5, p=0.9, tok=0x2000, tau=1.0: L.e3_sample_restricted(
         0x1000, dtype, 4, 64, 64, None, tau, k, p, 1, 0, tok, None, None, None)
-    assert call(dtype=0) == -3            # fp32 logits: E3_ERR_DTYPE
+    assert call(dtype=0, k=0) == -5       # fp32 rows are served for 1 <= top_k <= 256 only
+    assert call(dtype=0, k=257) == -5
+    assert call(dtype=7) == -3
     assert call(k=-1) == -5
     assert call(p=0.0) == -5 and call(p=float("nan")) == -5 and call(p=-0.5) == -5
     assert call(tau=0.0) == -5
@@ -184,3 +186,117 @@ def test_seeded_random_settings(i, V, rows, k, p, tau, sigma, shift):
     lg = (torch.randn((rows, pitch), generator=g, device=DEV) * sigma + shift).to(torch.bfloat16)[:, :V]
     tau_rows = None if i % 2 else (tau * (0.5 + torch.rand(rows, generator=g, device=DEV))).float()
     check(lg, tau_rows, tau, k, p, seed=i, row_base=i << 20, label=f"case {i}: {rows}x{V} k={k} p={p} tau={tau}")
+
+
+# ---------------------------------------------------------------- fp32 rows and the selection path
+# top_k <= 256 is served by selection (chunk maxima, a lower bound from the thread maxima, an
+# exact radix select) for bf16 and fp32 rows alike; larger k and top-p alone need the bf16 histogram.
+@pytest.mark.gpu
+@pytest.mark.parametrize("k,p", [(50, 1.0), (50, 0.95), (1, 1.0), (256, 0.9), (3, 0.5), (200, 1e-4)])
+def test_fp32_decode_rows_full_vocab(k, p):
+    w = wl.decode_step(DEV, seed=2, prompts=8, rollouts=8)
+    lg = w.logits.float() + 1e-3 * torch.randn(w.logits.shape, device=DEV,
+                                               generator=torch.Generator(device=DEV).manual_seed(k))
+    check(lg, w.tau_rows, 1.0, k, p, seed=19, row_base=1 << 35, label=f"fp32 decode k={k} p={p}")
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("dtype", [torch.bfloat16, torch.float32])
+@pytest.mark.parametrize("V", [1, 3, 4, 5, 8, 9, 1000, 4096, 8200 + 4, 70_001 + 7, 300_000])
+def test_selection_shapes_and_tails(V, dtype):
+    g = torch.Generator(device=DEV).manual_seed(V + 1)
+    per = 8 if dtype == torch.bfloat16 else 4
+    pitch = -(-V // per) * per
+    lg = (torch.randn((5, pitch), generator=g, device=DEV) * 2.5).to(dtype)[:, :V]
+    for k, p in ((7, 0.9), (1, 1.0), (256, 1.0), (64, 0.3)):
+        check(lg, None, 0.8, k, p, V, 3, f"select V={V} {dtype} k={k} p={p}")
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("dtype", [torch.bfloat16, torch.float32])
+def test_selection_repeated_values_plateaus_and_signed_zeros(dtype):
+    g = torch.Generator(device=DEV).manual_seed(9)
+    vals = torch.tensor([3.0, 2.5, 2.5, 1.0, 0.0, -0.0, -1.0, -1.0, -4.0], device=DEV)
+    idx = torch.randint(0, vals.numel(), (12, 5000), generator=g, device=DEV)
+    lg = vals[idx].to(dtype)
+    for k, p in [(1, 1.0), (10, 1.0), (200, 0.9), (256, 0.999), (256, 0.2)]:
+        check(lg, None, 1.2, k, p, 3, 77, f"select repeated {dtype} k={k} p={p}")
+    # zeros of both signs around the cut: +0 ranks above -0
+    z = torch.zeros((6, 3000), device=DEV)
+    z[:, ::3] = -0.0
+    z[:, 5::7] = 0.5
+    z[:, 1::11] = -0.25
+    check(z.to(dtype), None, 0.9, 256, 1.0, 4, 5, f"select zeros {dtype}")
+    check(z.to(dtype), None, 0.9, 255, 0.95, 4, 5, f"select zeros {dtype} p")
+    # one level holds the whole row: the cut level is a plateau, its pos-th column is counted out
+    same = torch.full((4, 2048), 0.5, device=DEV).to(dtype)
+    r = check(same, None, 1.0, 5, 0.3, 1, 0, f"select all equal {dtype}")
+    assert (r.kept == 2048).all()
+    wide = torch.full((2, 40_000), -1.5, device=DEV)
+    wide[:, 17] = 2.0
+    r = check(wide.to(dtype), None, 1.0, 3, 1.0, 2, 0, f"select plateau under one peak {dtype}")
+    assert (r.kept == 40_000).all()
+    # rows without a non-negative value, and values down in the subnormals
+    neg = (torch.randn((6, 9000), generator=g, device=DEV) * 3 - 40.0).to(dtype)
+    check(neg, None, 1.0, 40, 0.9, 6, 0, f"select all negative {dtype}")
+    tiny = (torch.randn((4, 3000), generator=g, device=DEV) * 1e-39).to(dtype)
+    check(tiny, None, 1.0, 9, 1.0, 6, 0, f"select subnormal {dtype}")
+
+
+@pytest.mark.gpu
+def test_selection_on_sorted_and_blocky_rows():
+    # adversarial for the lower bound: the largest values sit next to each other (one chunk holds
+    # many kept columns) or are spread so that single threads hold several of them
+    V = 151_936
+    asc = torch.arange(V, device=DEV, dtype=torch.float32) * 1e-4
+    rows = torch.stack([asc, asc.flip(0), torch.roll(asc, 12345), (asc % 7.0) + (asc > 15.0) * 3.0])
+    for dtype in (torch.float32, torch.bfloat16):
+        for k in (1, 17, 256):
+            check(rows.to(dtype), None, 0.5, k, 0.97, 8, 9, f"select sorted {dtype} k={k}")
+
+
+@pytest.mark.gpu
+def test_selection_widest_row():
+    V = 1_040_384
+    g = torch.Generator(device=DEV).manual_seed(45)
+    lg = (torch.randn((2, V), generator=g, device=DEV) * 2.5)
+    check(lg, None, 0.9, 50, 0.95, 8, 1, "select widest fp32")
+    check(lg.to(torch.bfloat16), None, 0.9, 256, 0.95, 8, 1, "select widest bf16")
+    same = torch.full((1, V), -1.5, device=DEV)
+    r = check(same, None, 1.0, 3, 0.5, 2, 0, "select widest fp32, all equal")
+    assert (r.kept == V).all()
+
+
+def _random_select_cases(n, seed):
+    rng = np.random.default_rng(seed)
+    out = []
+    for i in range(n):
+        V = int(rng.choice([rng.integers(1, 100), rng.integers(100, 9000), rng.integers(9000, 60_000)]))
+        rows = int(rng.integers(1, 10))
+        k = int(rng.choice([1, 2, rng.integers(3, 257), 256]))
+        p = float(rng.choice([1.0, 0.999, 0.9, 0.5, 0.1, 1e-4]))
+        out.append((i, V, rows, k, p, float(rng.choice([0.1, 1.0, 4.0, 60.0])), float(rng.choice([0.3, 3.0, 10.0])),
+                    float(rng.choice([0.0, 0.0, -8.0, 8.0])), bool(rng.integers(0, 2))))
+    return out
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("i,V,rows,k,p,tau,sigma,shift,coarse", _random_select_cases(40, 78))
+def test_seeded_random_fp32_settings(i, V, rows, k, p, tau, sigma, shift, coarse):
+    g = torch.Generator(device=DEV).manual_seed(900 + i)
+    pitch = -(-V // 4) * 4 + 4 * (i % 2)
+    lg = (torch.randn((rows, pitch), generator=g, device=DEV) * sigma + shift)
+    if coarse:                                     # few distinct values: levels with many columns
+        lg = torch.round(lg * 4) / 4
+    lg = lg[:, :V]
+    tau_rows = None if i % 2 else (tau * (0.5 + torch.rand(rows, generator=g, device=DEV))).float()
+    check(lg, tau_rows, tau, k, p, seed=i, row_base=i << 21, label=f"fp32 case {i}: {rows}x{V} k={k} p={p} tau={tau}")
+
+
+@pytest.mark.gpu
+def test_fp32_rows_need_a_small_top_k():
+    lg = torch.zeros((2, 64), device=DEV)
+    for k in (0, 257, 1000):
+        with pytest.raises(e3.E3Error) as ei:
+            e3.e3_sample_restricted(lg, None, 1.0, k, 0.9, 1, 0)
+        assert ei.value.status == -5
