@@ -144,7 +144,8 @@ int e3_sample_entropy_noalloc(const void* logits, int dtype, int64_t rows, int64
  * Rollout-side call with truncation: sample one token per row from the temperature-
  * scaled softmax restricted to the top-k and / or top-p (nucleus) part of the row.
  * The paper samples unrestricted (Section 5.1); this call covers the truncations that
- * rollout engines offer.  bf16 logits only (E3_ERR_DTYPE for E3_F32).
+ * rollout engines offer.  bf16 rows take every setting; fp32 rows need a count cut of
+ * 1 <= top_k <= 256 (with or without top_p), anything else on fp32 rows is E3_ERR_VALUE.
  *
  * Definition (on value levels, so that it does not depend on the order of equal logits):
  *   a level is the set of columns storing one bit pattern; levels are ranked by value,
@@ -169,7 +170,10 @@ int e3_sample_entropy_noalloc(const void* logits, int dtype, int64_t rows, int64
  * Logits must be finite (inf / NaN patterns are ignored as levels; a row without any
  *   finite logit gives token 0, logp NaN, kept 0).  Other arguments, alignment rules and
  *   errors as for e3_sample_entropy; top_k < 0 or top_p not in (0, inf): E3_ERR_VALUE.
- * One workgroup of 1024 threads and 128 KiB of LDS per row.
+ * One workgroup of 1024 threads per row.  With 1 <= top_k <= 256 the row is read once
+ * (vector maxima kept in LDS, the few vectors that can hold one of the k largest read
+ * again, exact selection among those); otherwise (bf16 only) a histogram over the 2^16
+ * stored patterns in 128 KiB of LDS, one to three sweeps of the row.
  */
 int e3_sample_restricted(const void* logits, int dtype, int64_t rows, int64_t V, int64_t row_stride,
                          const float* tau_rows, float tau_scalar, int32_t top_k, float top_p,
