@@ -536,6 +536,36 @@ def test_unusable_workspace_falls_back_to_whole_rows():
     assert torch.allclose(first[2], want[2], rtol=1e-5, atol=0)
 
 
+def test_small_batches_on_many_streams_at_once():
+    # the library holds no state between or across calls: small-batch calls issued on twenty
+    # streams at once, each with its own workspace, give every stream the bits of a call made alone
+    V = 151_936
+    g = torch.Generator(device=DEV).manual_seed(61)
+    lg = (torch.randn((24, V), generator=g, device=DEV) * 3).to(torch.bfloat16)
+    tgt = torch.randint(0, V, (24,), generator=g, device=DEV, dtype=torch.int32)
+    shapes = [1, 3, 8, 24, 16, 5]
+    alone = {}
+    for i, rows in enumerate(shapes):
+        alone[i] = (e3.e3_sample_entropy(lg[:rows], None, 0.9, seed=7, row_base=100 * i),
+                    e3.e3_logprob_entropy(lg[:rows], tgt[:rows], None, None, 0.9))
+    torch.cuda.synchronize()
+    streams = [torch.cuda.Stream(device=DEV) for _ in range(20)]
+    ws = [(e3.new_workspace(24, V, DEV), e3.new_workspace(24, V, DEV)) for _ in streams]
+    got = []
+    for rep in range(3):
+        for k, st in enumerate(streams):
+            i = (k + rep) % len(shapes)
+            rows = shapes[i]
+            with torch.cuda.stream(st):
+                a = e3.e3_sample_entropy(lg[:rows], None, 0.9, seed=7, row_base=100 * i, workspace=ws[k][0])
+                b = e3.e3_logprob_entropy(lg[:rows], tgt[:rows], None, None, 0.9, workspace=ws[k][1])
+            got.append((i, a, b))
+    torch.cuda.synchronize()
+    for i, a, b in got:
+        for x, y in zip(a + b, alone[i][0] + alone[i][1]):
+            assert torch.equal(x, y)
+
+
 def test_read_probe_reads_every_word():
     g = torch.Generator(device=DEV).manual_seed(41)
     for n in (0, 4, 4 * 2048 * 256 + 12, 1_000_004):                    # 32-bit words, multiples of 4
