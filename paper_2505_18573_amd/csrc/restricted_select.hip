@@ -10,7 +10,7 @@
 //   1. one streaming read of the row leaves the maximum of every chunk of columns in LDS
 //      (plain vector maxima: about two instructions per column, no atomics) and every
 //      thread's own maximum in a register;
-//   2. theta = the k-th largest of the 1024 thread maxima is a lower bound of the k-th
+//   2. theta, a value that at least k of the thread maxima reach, is a lower bound of the k-th
 //      largest column (k different threads hold a column at or above it), and a tight one:
 //      only the few chunks whose maximum reaches theta can hold kept columns;
 //   3. the columns at or above theta are read again from those chunks and listed in LDS; an
@@ -27,8 +27,17 @@
 namespace e3 {
 namespace {
 
-constexpr int kSThreads = 1024;
+// Threads per row.  Measured on MI355X, 512 rows x 151,936, top-k 50: 512 threads with up to
+// 128 registers each (two workgroups per compute unit, nothing spilled) 49.9 us for bf16 rows
+// and 80 us for fp32 rows; 1024 threads held to 64 registers (the same two workgroups per
+// compute unit; a dozen spilled, whose reloads queue behind the streaming) 61.7 - 67 us and
+// 82 - 112 us.
+#ifndef E3_SEL_THREADS
+#define E3_SEL_THREADS 512
+#endif
+constexpr int kSThreads = E3_SEL_THREADS;
 constexpr int kSWaves = kSThreads / 64;
+constexpr int kSBatch = 4096 / kSThreads;          // 16-byte requests a thread keeps in flight: 64 KiB per workgroup
 constexpr int kSMaxK = 256;             // top_k served here; the gt-list holds at most kSMaxK - 1 columns
 constexpr int kSEqCap = 64;             // columns of the cut level listed for a direct pick
 constexpr int kSListCap = 2048;         // candidates (columns at or above theta) listed in LDS
@@ -52,7 +61,7 @@ __device__ __forceinline__ uint32_t f32_of_key(uint32_t key)
 struct SelBf16 {
     typedef uint16_t Stored;
     static constexpr int kElems = 8;
-    static constexpr int kChunksPerThreadMax = 20;   // 40 KiB of chunk maxima
+    static constexpr int kChunksPerThreadMax = 20 * 1024 / kSThreads;   // 40 KiB of chunk maxima
     static constexpr int kKeyBits = 16;              // significant key bits, from the top
     static __device__ __forceinline__ uint32_t elem_bits(const u32x4& v, int j)   // as binary32
     {
@@ -73,7 +82,7 @@ struct SelBf16 {
 struct SelF32 {
     typedef uint32_t Stored;
     static constexpr int kElems = 4;
-    static constexpr int kChunksPerThreadMax = 10;   // 40 KiB of chunk maxima
+    static constexpr int kChunksPerThreadMax = 10 * 1024 / kSThreads;   // 40 KiB of chunk maxima
     static constexpr int kKeyBits = 32;
     static __device__ __forceinline__ uint32_t elem_bits(const u32x4& v, int j)
     {
@@ -175,10 +184,10 @@ struct SelArgs {
     int chunks;           // chunks per thread
 };
 
-// Two workgroups of sixteen waves per compute unit need eight waves per SIMD: at most 64
-// vector and 96 scalar registers per wave (gfx9 SIMDs hold 800 scalar registers).
+// Two workgroups per compute unit: kSWaves / 2 waves per SIMD, which bounds the registers a
+// wave may take (512 / that many vector registers, 800 / that many scalar ones).
 template <typename T>
-__global__ __launch_bounds__(kSThreads) __attribute__((amdgpu_waves_per_eu(8, 8)))
+__global__ __launch_bounds__(kSThreads) __attribute__((amdgpu_waves_per_eu(kSWaves / 2, kSWaves / 2)))
 void sample_select_kernel(SelArgs a)
 {
     extern __shared__ __align__(16) unsigned char dyn[];
@@ -198,7 +207,7 @@ void sample_select_kernel(SelArgs a)
     const uint64_t grow = a.row_base + (uint64_t)row;
 
     // ---- 1. chunk maxima ------------------------------------------------------------------
-    // chunk j of thread t = vectors t + 1024 (j G + g), g < G.  Maxima are taken as floats
+    // chunk j of thread t = vectors t + kSThreads (j G + g), g < G.  Maxima are taken as floats
     // (NaN operands drop out of v_max3); +inf is dealt with below; a maximum of zero is
     // recorded as +0, whichever zero it was.
     auto vec_key_max = [&](int64_t v, const u32x4& x) -> uint32_t {
@@ -219,21 +228,21 @@ void sample_select_kernel(SelArgs a)
         }
         return key;
     };
-    // Vector slots s = j G + g of this thread, four requests in flight at a time.
+    // Vector slots s = j G + g of this thread, kSBatch requests in flight at a time.
     uint32_t tmax = 0u;
     {
         const int nslots = CPT * G;
         uint32_t m = 0u;                                          // maximum of the chunk being filled
-        for (int s0 = 0; s0 < nslots; s0 += 4) {
-            u32x4 x[4];
-            int64_t vv[4];
+        for (int s0 = 0; s0 < nslots; s0 += kSBatch) {
+            u32x4 x[kSBatch];
+            int64_t vv[kSBatch];
 #pragma unroll
-            for (int u = 0; u < 4; ++u) {
+            for (int u = 0; u < kSBatch; ++u) {
                 vv[u] = (int64_t)tid + (int64_t)kSThreads * (s0 + u);
                 x[u] = (s0 + u < nslots && vv[u] < nvec) ? rv[vv[u]] : u32x4{0u, 0u, 0u, 0u};
             }
 #pragma unroll
-            for (int u = 0; u < 4; ++u) {
+            for (int u = 0; u < kSBatch; ++u) {
                 const int sl = s0 + u;
                 if (sl < nslots) {
                     if (vv[u] < nvec) { const uint32_t k1 = vec_key_max(vv[u], x[u]); m = k1 > m ? k1 : m; }
@@ -263,9 +272,9 @@ void sample_select_kernel(SelArgs a)
         }
         return;
     }
-    // Each wave takes the m-th largest of its lanes' maxima, m = ceil(k / 16), by striking the
-    // largest m - 1 times; the smallest of the sixteen results has 16 m >= k threads at or above
-    // it.  No atomics, one barrier.  (The exact k-th largest of the 1024 would be a little
+    // Each wave takes the m-th largest of its lanes' maxima, m = ceil(k / kSWaves), by striking the
+    // largest m - 1 times; the smallest of the waves' results has kSWaves m >= k threads at or above
+    // it.  No atomics, one barrier.  (The exact k-th largest of the thread maxima would be a little
     // tighter; it costs two to four histogram passes with their barriers.)
     const int k_req = a.top_k < kSMaxK ? a.top_k : kSMaxK;
     uint32_t theta;
@@ -324,22 +333,41 @@ void sample_select_kernel(SelArgs a)
     if (tid == 0) sh.list_n = 0;
     __syncthreads();
     {
-        // qualifying vectors of this thread, requested four at a time
-        int64_t vq[4];
-        int nq = 0;
-        auto flush = [&]() {
+        // The thread's qualifying chunks as a bit mask; their vectors are then walked four at a
+        // time with fixed register slots (a register array indexed by a running count would
+        // live in scratch memory, and each of its accesses would queue behind the other rows'
+        // streaming).  All lanes of a wave take part in every round: the slot reservation is
+        // a wave-wide operation.
+        static_assert(T::kChunksPerThreadMax <= 64, "one mask bit per chunk");
+        uint64_t qmask = 0u;
+        for (int j = 0; j < CPT; ++j)
+            qmask |= (uint64_t)(T::unpack_upper(cmax[(size_t)j * kSThreads + tid]) >= theta) << j;
+        int j = qmask != 0u ? __builtin_ctzll(qmask) : -1, g = 0;
+        while (__any(j >= 0)) {
+            int64_t vq[4];
+            bool on[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                vq[u] = (int64_t)tid + (int64_t)kSThreads * ((int64_t)(j < 0 ? 0 : j) * G + g);
+                on[u] = j >= 0 && vq[u] < nvec;
+                if (j >= 0 && (++g == G || !on[u])) {              // next qualifying chunk
+                    g = 0;
+                    qmask &= qmask - 1u;
+                    j = qmask != 0u ? __builtin_ctzll(qmask) : -1;
+                }
+            }
             u32x4 x[4];
 #pragma unroll
-            for (int u = 0; u < 4; ++u) x[u] = u < nq ? rv[vq[u]] : u32x4{0u, 0u, 0u, 0u};
+            for (int u = 0; u < 4; ++u) x[u] = on[u] ? rv[vq[u]] : u32x4{0u, 0u, 0u, 0u};
             // count my candidates, reserve a run of slots for the wave, write mine in order
             uint32_t ok_mask = 0u;
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
 #pragma unroll
                 for (int e = 0; e < T::kElems; ++e) {
-                    const int64_t col = (u < nq ? vq[u] : 0) * T::kElems + e;
+                    const int64_t col = vq[u] * T::kElems + e;
                     const uint32_t key = key_of_f32(T::elem_bits(x[u], e));
-                    ok_mask |= (uint32_t)(u < nq && col < V && key >= theta) << (u * T::kElems + e);
+                    ok_mask |= (uint32_t)(on[u] && col < V && key >= theta) << (u * T::kElems + e);
                 }
             }
             const int mine = __popc(ok_mask);
@@ -367,16 +395,7 @@ void sample_select_kernel(SelArgs a)
                     }
                 }
             }
-            nq = 0;
-        };
-        // all lanes of a wave flush together (the slot reservation is a wave-wide operation)
-        for (int sl = 0; sl < CPT * G; ++sl) {
-            const int64_t v = (int64_t)tid + (int64_t)kSThreads * sl;
-            const bool q = v < nvec && T::unpack_upper(cmax[(size_t)(sl / G) * kSThreads + tid]) >= theta;
-            if (q) vq[nq++] = v;
-            if (__any(nq == 4)) flush();
         }
-        if (__any(nq > 0)) flush();
     }
     __syncthreads();
     const int n_list = sh.list_n;
@@ -447,16 +466,19 @@ void sample_select_kernel(SelArgs a)
     __syncthreads();
     const int n = count_gt;                                        // == sh.gt_n
     // sort by (key descending, column ascending): rank by counting, the n x n comparisons spread
-    // over all threads (entry i = tid mod 256 against a quarter of the others each)
+    // over all threads (entry i = tid mod 256 against one part of the others each)
     if (tid < kSMaxK) sh.rank[tid] = 0;
     __syncthreads();
     {
-        const int i = tid & (kSMaxK - 1), quarter = tid / kSMaxK;
+        constexpr int kParts = kSThreads / kSMaxK;
+        static_assert(kParts >= 1 && kParts * kSMaxK == kSThreads, "whole parts");
+        const int i = tid & (kSMaxK - 1), part = tid / kSMaxK;
         if (i < n) {
             const uint32_t mk = sh.gt_key[i];
             const int32_t mc = sh.gt_col[i];
-            const int e_begin = quarter * ((n + 3) / 4);
-            const int e_end = e_begin + (n + 3) / 4 < n ? e_begin + (n + 3) / 4 : n;
+            const int per = (n + kParts - 1) / kParts;
+            const int e_begin = part * per;
+            const int e_end = e_begin + per < n ? e_begin + per : n;
             int r = 0;
 #pragma unroll 8
             for (int e = e_begin; e < e_end; ++e) {
