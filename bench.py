@@ -113,7 +113,7 @@ def main() -> int:
                     help="skip the kernel timings on configs 3 (dynamic budgets), 4 (training pass) and "
                          "5 (large decode batch) that the default run reports in `other_configs`")
     ap.add_argument("--restricted", action="store_true",
-                    help="also time e3_sample_restricted (top-k 50, top-p 0.95) on the same batches and "
+                    help="also time e3_sample_restricted (top-k / top-p settings, bf16 and fp32 rows) on the same batches and "
                          "report it in a `restricted_sampling` object; not part of the step")
     ap.add_argument("--sizes", action="store_true",
                     help="also time the two vocabulary-pass kernels and the read probe on other batch "
@@ -501,14 +501,19 @@ def restricted_leg(e3, batches, stream, reps: int = 50):
     lp = torch.empty(ROWS, dtype=torch.float32, device=dev)
     kept = torch.empty(ROWS, dtype=torch.int32, device=dev)
     res = {}
-    for name, k, p in (("top_k50", 50, 1.0), ("top_k50_top_p0.95", 50, 0.95), ("top_p0.9", 0, 0.9)):
+    f32 = [b.logits.float() for b in batches[:4]]            # fp32 rows of the same batches (1.2 GB)
+    settings = (("top_k50", 50, 1.0, 2), ("top_k50_top_p0.95", 50, 0.95, 2), ("top_k256_top_p0.9", 256, 0.9, 2),
+                ("top_p0.9", 0, 0.9, 2), ("f32_top_k50", 50, 1.0, 4), ("f32_top_k50_top_p0.95", 50, 0.95, 4))
+    for name, k, p, esz in settings:
+        rot = len(batches) if esz == 2 else len(f32)
         evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
                for _ in range(reps)]
         for i in range(5 + reps):
-            b = batches[i % len(batches)]
+            b = batches[i % rot]
+            logits = b.logits if esz == 2 else f32[i % rot]
             if i >= 5:
                 evs[i - 5][0].record(stream)
-            e3.e3_sample_restricted(b.logits, b.tau_rows, 1.0, k, p, seed=7, row_base=i * ROWS,
+            e3.e3_sample_restricted(logits, b.tau_rows, 1.0, k, p, seed=7, row_base=i * ROWS,
                                     token_out=tok, logp_out=lp, kept_out=kept)
             if i >= 5:
                 evs[i - 5][1].record(stream)
@@ -516,8 +521,8 @@ def restricted_leg(e3, batches, stream, reps: int = 50):
         ms = sorted(a.elapsed_time(b) for a, b in evs)
         avg = sum(ms) / len(ms)
         res[name] = {"avg_ms": avg, "median_ms": ms[len(ms) // 2], "rows_per_s": ROWS / (avg * 1e-3),
-                     "logit_GBps": ROWS * V * 2 / (avg * 1e-3) / 1e9,
-                     "frac_of_hbm_peak": ROWS * V * 2 / (avg * 1e-3) / 1e9 / HBM_PEAK_GBPS,
+                     "logit_GBps": ROWS * V * esz / (avg * 1e-3) / 1e9,
+                     "frac_of_hbm_peak": ROWS * V * esz / (avg * 1e-3) / 1e9 / HBM_PEAK_GBPS,
                      "mean_kept": float(kept.float().mean().item())}
     return res
 
