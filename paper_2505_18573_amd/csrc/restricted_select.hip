@@ -21,17 +21,20 @@
 //      taken, exactly as the definition says; the cut level takes part with its count.
 // Every count is exact and every mass fp64, as in restricted.hip; a row with enormous
 // plateaus of equal values is slow (its chunks all qualify) but takes the same path.
+// Steps 3 (from the radix select on) and 4 exist twice: workgroup-wide, with a barrier after
+// every short phase, and - for a list of at most 256 candidates and top_k <= 64, the usual
+// case - inside one wave with the kept columns one per lane (finish_in_one_wave below).
 #include "vocab_common.h"
 #include "vocab_pass.h"
 
 namespace e3 {
 namespace {
 
-// Threads per row.  Measured on MI355X, 512 rows x 151,936, top-k 50: 512 threads with up to
-// 128 registers each (two workgroups per compute unit, nothing spilled) 49.9 us for bf16 rows
-// and 80 us for fp32 rows; 1024 threads held to 64 registers (the same two workgroups per
-// compute unit; a dozen spilled, whose reloads queue behind the streaming) 61.7 - 67 us and
-// 82 - 112 us.
+// Threads per row.  Measured on MI355X, 512 rows x 151,936, top-k 50, workgroup-wide steps
+// throughout: 512 threads with up to 128 registers each (two workgroups per compute unit,
+// nothing spilled) 49.9 us for bf16 rows and 80 us for fp32 rows; 1024 threads held to 64
+// registers (the same two workgroups per compute unit; a dozen spilled, whose reloads queue
+// behind the streaming) 61.7 - 67 us and 82 - 112 us.
 #ifndef E3_SEL_THREADS
 #define E3_SEL_THREADS 512
 #endif
@@ -98,7 +101,7 @@ struct SelF32 {
     }
 };
 
-struct SelShared {
+struct alignas(16) SelShared {
     uint32_t hist[256];
     uint32_t prefix, k_rem, n_eq_last;      // radix select state
     uint32_t n_total;                        // candidates seen by the first pass
@@ -183,6 +186,207 @@ struct SelArgs {
     int group;            // vectors per chunk
     int chunks;           // chunks per thread
 };
+
+// ---------------------------------------------------------------------------
+// The rest of a row in one wave, for a short candidate list (at most kSoloList entries in
+// LDS) and a small count cut (top_k <= kSoloK, so fewer than 64 columns stand above the cut
+// level: one per lane, and lane 63 is free for the cut level itself).  Same steps and same
+// arithmetic as the workgroup-wide code in the kernel below; what changes is where the
+// data sit: after the exact radix select for kappa the columns above it live one per lane,
+// are ranked against each other through lane broadcasts, and masses, cuts, race and pick are
+// wave scans, ballots and lane reads.  No workgroup barrier is involved (the other waves
+// have left), and what goes through LDS is ordered by the wave's own program order.
+// ---------------------------------------------------------------------------
+constexpr int kSoloList = 256;
+constexpr int kSoloK = 64;
+
+__device__ __forceinline__ double read_lane_f64(double v, int src_lane)
+{
+    const long long b = __double_as_longlong(v);
+    const int lo = __builtin_amdgcn_readlane((int)(b & 0xFFFFFFFFll), src_lane);
+    const int hi = __builtin_amdgcn_readlane((int)(b >> 32), src_lane);
+    return __longlong_as_double(((long long)hi << 32) | (long long)(uint32_t)lo);
+}
+
+template <typename T>
+__device__ __forceinline__ void finish_in_one_wave(const SelArgs& a, SelShared& sh, const uint32_t* lkey,
+                                                   const int32_t* lcol, int n_list, int k_req, int64_t row,
+                                                   uint64_t grow, double inv_tau, float c, int lane)
+{
+    auto lds_order = []() {
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+    };
+    const unsigned long long below = (1ull << lane) - 1ull;        // lanes before mine
+
+    // kappa: the k-th largest listed column, 8 bits per pass
+    const uint32_t k_eff = (uint32_t)(n_list < k_req ? n_list : k_req);   // fewer than k finite columns: all of them
+    if (lane == 0) { sh.prefix = 0u; sh.k_rem = k_eff; }
+    for (int pass = 0; pass < T::kKeyBits / 8; ++pass) {
+        const int shift = 24 - 8 * pass;
+        reinterpret_cast<uint4*>(sh.hist)[lane] = uint4{0u, 0u, 0u, 0u};
+        lds_order();
+        const uint32_t prefix = sh.prefix;
+        for (int e = lane; e < n_list; e += 64) {
+            const uint32_t key = lkey[e];
+            if (pass == 0 || (key >> (shift + 8)) == prefix) atomicAdd(&sh.hist[(key >> shift) & 255u], 1u);
+        }
+        lds_order();
+        select_digit(sh, lane);
+        lds_order();
+    }
+    const uint32_t kappa = T::kKeyBits == 32 ? sh.prefix
+                         : ((sh.prefix << 16) | ((sh.prefix & 0x8000u) ? 0u : 0xFFFFu));
+    const int n_cut = (int)sh.n_eq_last;                           // columns on the cut level
+    const int n = (int)(k_eff - sh.k_rem);                         // columns above it: fewer than k
+
+    // the columns above kappa, one per lane in list order; those on kappa's level into their list
+    uint32_t key_i = 0u;
+    int32_t col_i = 0;
+    {
+        int n_gt = 0, n_eq = 0;
+        for (int e0 = 0; e0 < n_list; e0 += 64) {
+            const int e = e0 + lane;
+            const uint32_t key = e < n_list ? lkey[e] : 0u;
+            const int32_t col = e < n_list ? lcol[e] : 0;
+            const bool gt = e < n_list && key > kappa;
+            const unsigned long long gm = __ballot(gt);
+            if (gt) {
+                const int slot = n_gt + __popcll(gm & below);
+                sh.gt_key[slot] = key;
+                sh.gt_col[slot] = col;
+            }
+            n_gt += __popcll(gm);
+            const bool eq = e < n_list && key == kappa;
+            const unsigned long long em = __ballot(eq);
+            if (eq) {
+                const int slot = n_eq + __popcll(em & below);
+                if (slot < kSEqCap) sh.eq_col[slot] = col;
+            }
+            n_eq += __popcll(em);
+        }
+        lds_order();
+        if (lane < n) { key_i = sh.gt_key[lane]; col_i = sh.gt_col[lane]; }
+    }
+    // rank by (value descending, column ascending): each lane counts the lanes ahead of it; one
+    // 64-bit comparison per pair on (key, inverted column)
+    const uint64_t order_i = ((uint64_t)key_i << 32) | (uint32_t)~col_i;
+    int rank = 0;
+    for (int e = 0; e < n; ++e) {
+        const uint32_t ok = (uint32_t)__builtin_amdgcn_readlane((int)key_i, e);
+        const uint32_t oc = (uint32_t)__builtin_amdgcn_readlane(~col_i, e);
+        rank += (((uint64_t)ok << 32) | oc) > order_i;
+    }
+    if (lane < n) { sh.st_key[rank] = key_i; sh.st_col[rank] = col_i; }
+    lds_order();
+    const bool have = lane < n;
+    const uint32_t skey = have ? sh.st_key[lane] : 0u;             // lane = rank from here on
+    const int32_t scol = have ? sh.st_col[lane] : 0;
+
+    // masses in rank order (fp64), cuts
+    const uint32_t key1 = n > 0 ? (uint32_t)__builtin_amdgcn_readlane((int)skey, 0) : kappa;   // the row's highest level
+    const double z1 = (double)__uint_as_float(f32_of_key(key1));
+    const double z_cut = (double)__uint_as_float(f32_of_key(kappa));
+    const double w = have ? exp(((double)__uint_as_float(f32_of_key(skey)) - z1) * inv_tau) : 0.0;
+    double M = w;                                                   // inclusive prefix mass
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        const double o = __shfl_up(M, d, 64);
+        if (lane >= d) M += o;
+    }
+    const double M_gt = n > 0 ? read_lane_f64(M, n - 1) : 0.0;
+    const double w_cut = exp((z_cut - z1) * inv_tau);
+    const double M_k = M_gt + (double)n_cut * w_cut;               // mass of the top-k set
+    const uint32_t next_key = (uint32_t)__shfl_down((int)skey, 1, 64);
+    const uint32_t prev_key = (uint32_t)__shfl_up((int)skey, 1, 64);
+    int cut_index = kSMaxK;                                          // default: everything down to the cut level
+    if (a.top_p < 1.0f) {
+        // top-p on the renormalised top-k set: first level end whose cumulative mass reaches the target
+        const double Tm = (double)a.top_p * M_k;
+        const bool level_end = have && (lane == n - 1 || next_key != skey);
+        const unsigned long long reach = __ballot(level_end && M >= Tm);
+        if (reach != 0ull) cut_index = (int)__builtin_ctzll(reach);
+    }
+    const bool cut_level_kept = cut_index == kSMaxK;
+    const int kept_sorted = cut_level_kept ? n : cut_index + 1;    // sorted entries kept
+    const int kept_C = cut_level_kept ? n + n_cut : kept_sorted;
+    const double kept_M = cut_level_kept ? M_k : read_lane_f64(M, cut_index);
+
+    // race of the kept levels: a level's first lane scores it, lane 63 scores the cut level
+    const bool level_start = have && (lane == 0 || prev_key != skey);
+    const unsigned long long starts = __ballot(level_start);
+    const unsigned long long later = lane < 63 ? starts >> (lane + 1) : 0ull;
+    const int cnt = (later != 0ull ? lane + 1 + (int)__builtin_ctzll(later) : n) - lane;    // columns of my level
+    const float z1f = __uint_as_float(f32_of_key(key1));
+    const bool for_cut = lane == 63 && cut_level_kept;
+    float my_q = -1.0f;
+    int my_lvl = 0x7FFFFFFF;                                       // sorted index of the level's first entry; kSMaxK = cut level
+    if ((level_start && lane < kept_sorted) || for_cut) {
+        const uint32_t bits = f32_of_key(for_cut ? kappa : skey);
+        const uint32_t pat = T::pattern_of_bits(bits);
+        uint32_t w4[4];
+        philox4x32_10(pat >> 2, (uint32_t)grow, (uint32_t)(grow >> 32), 3u,
+                      (uint32_t)a.seed, (uint32_t)(a.seed >> 32), w4);
+        const int sel = pat & 3;
+        const uint32_t word = sel == 0 ? w4[0] : sel == 1 ? w4[1] : sel == 2 ? w4[2] : w4[3];
+        my_q = (float)(for_cut ? n_cut : cnt) * __builtin_amdgcn_exp2f((__uint_as_float(bits) - z1f) * c)
+             * inv_exp_variate(word);
+        my_lvl = for_cut ? kSMaxK : lane;
+    }
+#pragma unroll
+    for (int d = 32; d > 0; d >>= 1) {
+        const float oq = __shfl_xor(my_q, d, 64);
+        const int ol = __shfl_xor(my_lvl, d, 64);
+        if (oq > my_q || (oq == my_q && ol < my_lvl)) { my_q = oq; my_lvl = ol; }   // ties: the higher level
+    }
+    const float best_q = __builtin_bit_cast(float, __builtin_amdgcn_readfirstlane(__builtin_bit_cast(int, my_q)));
+    const int best_lvl = __builtin_amdgcn_readfirstlane(my_lvl);
+
+    // the column inside the winning level
+    uint32_t w4[4];
+    philox4x32_10(0u, (uint32_t)grow, (uint32_t)(grow >> 32), 4u, (uint32_t)a.seed, (uint32_t)(a.seed >> 32), w4);
+    const uint64_t k23 = (uint64_t)(w4[0] >> 9);
+    int tok = 0;
+    uint32_t tok_key = key1;
+    if (best_q >= 0.0f && best_lvl < kSMaxK) {
+        const int level_cnt = __builtin_amdgcn_readlane(cnt, best_lvl);
+        const int pos = (int)(((2u * k23 + 1u) * (uint64_t)level_cnt) >> 24);
+        tok = __builtin_amdgcn_readlane(scol, best_lvl + pos);     // a level's lanes are in column order
+        tok_key = (uint32_t)__builtin_amdgcn_readlane((int)skey, best_lvl);
+    } else if (best_q >= 0.0f) {
+        const int pos = (int)(((2u * k23 + 1u) * (uint64_t)n_cut) >> 24);
+        tok_key = kappa;
+        if (n_cut <= kSEqCap) {
+            // the pos-th smallest of the level's listed columns
+            const int32_t mc = lane < n_cut ? sh.eq_col[lane] : 0x7FFFFFFF;
+            int before = 0;
+            for (int e = 0; e < n_cut; ++e) before += __builtin_amdgcn_readlane(mc, e) < mc;
+            const unsigned long long hit = __ballot(lane < n_cut && before == pos);
+            tok = __builtin_amdgcn_readlane(mc, (int)__builtin_ctzll(hit | (1ull << 63)));
+        } else {
+            // a longer level inside the list: rank its columns against each other from LDS
+            for (int e0 = 0; e0 < n_list; e0 += 64) {
+                const int e = e0 + lane;
+                const bool mine = e < n_list && lkey[e] == kappa;
+                const int32_t mc = e < n_list ? lcol[e] : 0;
+                int before = 0;
+                if (mine)
+                    for (int f = 0; f < n_list; ++f) before += lkey[f] == kappa && lcol[f] < mc;
+                const unsigned long long hit = __ballot(mine && before == pos);
+                if (hit != 0ull) tok = __builtin_amdgcn_readlane(mc, (int)__builtin_ctzll(hit));
+            }
+        }
+    }
+    if (lane == 0) {
+        if (tok < 0 || tok >= a.V) tok = 0;
+        a.token_out[row] = tok;
+        if (a.kept_out) a.kept_out[row] = kept_C;
+        if (a.logp_out)
+            a.logp_out[row] = best_q >= 0.0f
+                ? (float)(((double)__uint_as_float(f32_of_key(tok_key)) - z1) * inv_tau - log(kept_M))
+                : __builtin_nanf("");
+    }
+}
 
 // Two workgroups per compute unit: kSWaves / 2 waves per SIMD, which bounds the registers a
 // wave may take (512 / that many vector registers, 800 / that many scalar ones).
@@ -400,6 +604,10 @@ void sample_select_kernel(SelArgs a)
     __syncthreads();
     const int n_list = sh.list_n;
     const bool listed = n_list <= kSListCap;
+    if (n_list <= kSoloList && k_req <= kSoloK) {                  // short list, small k: one wave finishes the row
+        if (wave == 0) finish_in_one_wave<T>(a, sh, lkey, lcol, n_list, k_req, row, grow, inv_tau, c, lane);
+        return;
+    }
     auto for_each_candidate = [&](auto&& f) {
         if (listed) {
             for (int e = tid; e < n_list; e += kSThreads) f(lkey[e], lcol[e]);

@@ -236,6 +236,17 @@ def test_selection_repeated_values_plateaus_and_signed_zeros(dtype):
     wide[:, 17] = 2.0
     r = check(wide.to(dtype), None, 1.0, 3, 1.0, 2, 0, f"select plateau under one peak {dtype}")
     assert (r.kept == 40_000).all()
+    # a cut level of 150 equal columns under ten larger ones, the rest far below: a short candidate
+    # list whose cut level is longer than the 64 columns that are listed apart; the level holds
+    # most of the mass, so most rows draw from it
+    lvl = torch.full((24, 3000), -20.0, device=DEV) - torch.rand((24, 3000), generator=g, device=DEV)
+    for r in range(24):
+        perm = torch.randperm(3000, generator=g, device=DEV)
+        lvl[r, perm[:150]] = 0.5
+        lvl[r, perm[150:160]] = 0.75 + 0.125 * torch.arange(10, device=DEV)
+    for k, p in [(20, 1.0), (20, 0.999), (64, 1.0), (11, 0.9)]:
+        r = check(lvl.to(dtype), None, 1.0, k, p, 12, 0, f"select long cut level {dtype} k={k} p={p}")
+        assert (r.kept == 160).all()
     # rows without a non-negative value, and values down in the subnormals
     neg = (torch.randn((6, 9000), generator=g, device=DEV) * 3 - 40.0).to(dtype)
     check(neg, None, 1.0, 40, 0.9, 6, 0, f"select all negative {dtype}")
