@@ -106,6 +106,7 @@ struct alignas(16) SelShared {
     uint32_t prefix, k_rem, n_eq_last;      // radix select state
     uint32_t n_total;                        // candidates seen by the first pass
     int gt_n, eq_n, list_n;                  // list fills
+    int pad_;                                // keeps the arrays below on 16-byte boundaries
     int rank[kSMaxK];
     uint32_t gt_key[kSMaxK];                 // unsorted, then sorted by (key desc, col asc)
     int32_t gt_col[kSMaxK];
@@ -120,6 +121,8 @@ struct alignas(16) SelShared {
     int token;
     uint32_t tmax_wave[kSWaves];
 };
+
+static_assert(offsetof(SelShared, gt_key) % 16 == 0 && offsetof(SelShared, gt_col) % 16 == 0, "read four at a time");
 
 // Largest unsigned value of the wave, returned wave-uniform (DPP butterfly as in wave_best).
 template <int kCtrl, int kRowMask = 0xF>
@@ -172,6 +175,20 @@ __device__ __forceinline__ void select_digit(SelShared& sh, int tid)
     }
 }
 
+// Inclusive prefix sum over the lanes of a wave: four shifts inside each row of sixteen lanes,
+// then lane 15 of a row into the next row and lane 31 into the upper half (lanes a shift does
+// not reach read zero).
+__device__ __forceinline__ int wave_prefix_sum(int v)
+{
+    v += dpp_i<0x111>(0, v);               // row_shr:1
+    v += dpp_i<0x112>(0, v);               // row_shr:2
+    v += dpp_i<0x114>(0, v);               // row_shr:4
+    v += dpp_i<0x118>(0, v);               // row_shr:8
+    v += dpp_i<kDppBcast15, 0xA>(0, v);
+    v += dpp_i<kDppBcast31, 0xC>(0, v);
+    return v;
+}
+
 struct SelArgs {
     const void* logits;
     int64_t rows, V, row_stride;
@@ -192,9 +209,10 @@ struct SelArgs {
 // LDS) and a small count cut (top_k <= kSoloK, so fewer than 64 columns stand above the cut
 // level: one per lane, and lane 63 is free for the cut level itself).  Same steps and same
 // arithmetic as the workgroup-wide code in the kernel below; what changes is where the
-// data sit: after the exact radix select for kappa the columns above it live one per lane,
-// are ranked against each other through lane broadcasts, and masses, cuts, race and pick are
-// wave scans, ballots and lane reads.  No workgroup barrier is involved (the other waves
+// data sit: the list is held in registers (four entries per lane), kappa is found bit by bit
+// with ballots, the columns above it then live one per lane, are ranked against each other
+// through lane broadcasts, and masses, cuts, race and pick are wave scans, ballots and lane
+// reads.  No workgroup barrier is involved (the other waves
 // have left), and what goes through LDS is ordered by the wave's own program order.
 // ---------------------------------------------------------------------------
 constexpr int kSoloList = 256;
@@ -219,51 +237,52 @@ __device__ __forceinline__ void finish_in_one_wave(const SelArgs& a, SelShared& 
     };
     const unsigned long long below = (1ull << lane) - 1ull;        // lanes before mine
 
-    // kappa: the k-th largest listed column, 8 bits per pass
-    const uint32_t k_eff = (uint32_t)(n_list < k_req ? n_list : k_req);   // fewer than k finite columns: all of them
-    if (lane == 0) { sh.prefix = 0u; sh.k_rem = k_eff; }
-    for (int pass = 0; pass < T::kKeyBits / 8; ++pass) {
-        const int shift = 24 - 8 * pass;
-        reinterpret_cast<uint4*>(sh.hist)[lane] = uint4{0u, 0u, 0u, 0u};
-        lds_order();
-        const uint32_t prefix = sh.prefix;
-        for (int e = lane; e < n_list; e += 64) {
-            const uint32_t key = lkey[e];
-            if (pass == 0 || (key >> (shift + 8)) == prefix) atomicAdd(&sh.hist[(key >> shift) & 255u], 1u);
-        }
-        lds_order();
-        select_digit(sh, lane);
-        lds_order();
+    // the list in registers: lane l holds entries l, l + 64, ... (key 0 = none: below every real key)
+    constexpr int kPerLane = kSoloList / 64;
+    uint32_t lk[kPerLane];
+    int32_t lc[kPerLane];
+#pragma unroll
+    for (int j = 0; j < kPerLane; ++j) {
+        const int e = lane + 64 * j;
+        lk[j] = e < n_list ? lkey[e] : 0u;
+        lc[j] = e < n_list ? lcol[e] : 0;
     }
-    const uint32_t kappa = T::kKeyBits == 32 ? sh.prefix
-                         : ((sh.prefix << 16) | ((sh.prefix & 0x8000u) ? 0u : 0xFFFFu));
-    const int n_cut = (int)sh.n_eq_last;                           // columns on the cut level
-    const int n = (int)(k_eff - sh.k_rem);                         // columns above it: fewer than k
+    // kappa, the k-th largest listed key, bit by bit from the top: the largest value that at
+    // least k keys reach (one ballot per register and bit; the keys' low bits follow the sign
+    // when only the upper kKeyBits are significant)
+    const int k_eff = n_list < k_req ? n_list : k_req;              // fewer than k finite columns: all of them
+    uint32_t kappa = 0u;
+    for (int b = 31; b >= 32 - T::kKeyBits; --b) {
+        const uint32_t cand = kappa | (1u << b);
+        int reach = 0;
+#pragma unroll
+        for (int j = 0; j < kPerLane; ++j) reach += __popcll(__ballot(lk[j] >= cand));
+        if (reach >= k_eff) kappa = cand;
+    }
+    if (T::kKeyBits < 32 && (kappa & 0x80000000u) == 0u) kappa |= 0xFFFFFFFFu >> T::kKeyBits;
 
     // the columns above kappa, one per lane in list order; those on kappa's level into their list
     uint32_t key_i = 0u;
     int32_t col_i = 0;
+    int n = 0, n_cut = 0;                                          // columns above kappa (fewer than k), columns on its level
     {
-        int n_gt = 0, n_eq = 0;
-        for (int e0 = 0; e0 < n_list; e0 += 64) {
-            const int e = e0 + lane;
-            const uint32_t key = e < n_list ? lkey[e] : 0u;
-            const int32_t col = e < n_list ? lcol[e] : 0;
-            const bool gt = e < n_list && key > kappa;
+#pragma unroll
+        for (int j = 0; j < kPerLane; ++j) {
+            const bool gt = lk[j] > kappa;
             const unsigned long long gm = __ballot(gt);
             if (gt) {
-                const int slot = n_gt + __popcll(gm & below);
-                sh.gt_key[slot] = key;
-                sh.gt_col[slot] = col;
+                const int slot = n + __popcll(gm & below);
+                sh.gt_key[slot] = lk[j];
+                sh.gt_col[slot] = lc[j];
             }
-            n_gt += __popcll(gm);
-            const bool eq = e < n_list && key == kappa;
+            n += __popcll(gm);
+            const bool eq = lk[j] == kappa;
             const unsigned long long em = __ballot(eq);
             if (eq) {
-                const int slot = n_eq + __popcll(em & below);
-                if (slot < kSEqCap) sh.eq_col[slot] = col;
+                const int slot = n_cut + __popcll(em & below);
+                if (slot < kSEqCap) sh.eq_col[slot] = lc[j];
             }
-            n_eq += __popcll(em);
+            n_cut += __popcll(em);
         }
         lds_order();
         if (lane < n) { key_i = sh.gt_key[lane]; col_i = sh.gt_col[lane]; }
@@ -575,16 +594,11 @@ void sample_select_kernel(SelArgs a)
                 }
             }
             const int mine = __popc(ok_mask);
-            int inc = mine;
-#pragma unroll
-            for (int d = 1; d < 64; d <<= 1) {
-                const int o = __shfl_up(inc, d, 64);
-                if (lane >= d) inc += o;
-            }
-            const int wave_total = __shfl(inc, 63, 64);
+            const int inc = wave_prefix_sum(mine);
+            const int wave_total = __builtin_amdgcn_readlane(inc, 63);
             int base = 0;
             if (lane == 63 && wave_total > 0) base = atomicAdd(&sh.list_n, wave_total);
-            base = __shfl(base, 63, 64);
+            base = __builtin_amdgcn_readlane(base, 63);
             int slot = base + inc - mine;
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
@@ -682,17 +696,19 @@ void sample_select_kernel(SelArgs a)
         static_assert(kParts >= 1 && kParts * kSMaxK == kSThreads, "whole parts");
         const int i = tid & (kSMaxK - 1), part = tid / kSMaxK;
         if (i < n) {
-            const uint32_t mk = sh.gt_key[i];
-            const int32_t mc = sh.gt_col[i];
-            const int per = (n + kParts - 1) / kParts;
+            // four entries per LDS read, one 64-bit comparison per pair on (key, inverted column)
+            const uint64_t mine = ((uint64_t)sh.gt_key[i] << 32) | (uint32_t)~sh.gt_col[i];
+            const int per = ((n + kParts - 1) / kParts + 3) & ~3;
             const int e_begin = part * per;
             const int e_end = e_begin + per < n ? e_begin + per : n;
             int r = 0;
-#pragma unroll 8
-            for (int e = e_begin; e < e_end; ++e) {
-                const uint32_t ok = sh.gt_key[e];
-                const int32_t oc = sh.gt_col[e];
-                r += (ok > mk) || (ok == mk && oc < mc);
+            for (int e = e_begin; e < e_end; e += 4) {
+                const uint4 ok = *reinterpret_cast<const uint4*>(&sh.gt_key[e]);
+                const int4 oc = *reinterpret_cast<const int4*>(&sh.gt_col[e]);
+                r += (((uint64_t)ok.x << 32) | (uint32_t)~oc.x) > mine;
+                r += e + 1 < e_end && (((uint64_t)ok.y << 32) | (uint32_t)~oc.y) > mine;
+                r += e + 2 < e_end && (((uint64_t)ok.z << 32) | (uint32_t)~oc.z) > mine;
+                r += e + 3 < e_end && (((uint64_t)ok.w << 32) | (uint32_t)~oc.w) > mine;
             }
             if (r != 0) atomicAdd(&sh.rank[i], r);
         }
