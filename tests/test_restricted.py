@@ -232,6 +232,10 @@ def test_selection_repeated_values_plateaus_and_signed_zeros(dtype):
     same = torch.full((4, 2048), 0.5, device=DEV).to(dtype)
     r = check(same, None, 1.0, 5, 0.3, 1, 0, f"select all equal {dtype}")
     assert (r.kept == 2048).all()
+    # the same inside a short candidate list: nothing above the cut level, 200 columns on it
+    same_small = torch.full((4, 200), 0.5, device=DEV).to(dtype)
+    r = check(same_small, None, 1.0, 5, 0.3, 1, 0, f"select all equal, short row {dtype}")
+    assert (r.kept == 200).all()
     wide = torch.full((2, 40_000), -1.5, device=DEV)
     wide[:, 17] = 2.0
     r = check(wide.to(dtype), None, 1.0, 3, 1.0, 2, 0, f"select plateau under one peak {dtype}")
