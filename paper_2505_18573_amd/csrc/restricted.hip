@@ -34,6 +34,7 @@ constexpr int kRThreads = 1024;
 constexpr int kRWaves = kRThreads / 64;
 constexpr int kBins = 32768;            // bit patterns of one sign
 constexpr int kOwn = kBins / kRThreads; // 32 consecutive bins per thread
+constexpr int kTrashBins = 64;          // words behind the window that take the other sign's patterns
 
 struct RaceBest {
     double q;        // n_j w_j / E_j, -1 = none
@@ -73,14 +74,20 @@ __device__ __forceinline__ void build_hist(const uint16_t* __restrict__ row, int
     const uint4 zero4 = {0u, 0u, 0u, 0u};
     for (int i = tid; i < kBins / 4; i += kRThreads) reinterpret_cast<uint4*>(hist)[i] = zero4;
     __syncthreads();
-    auto add = [&](uint32_t b16) {
-        const bool in_window = hi ? b16 < 0x8000u : b16 >= 0x8000u;
-        const uint32_t bin = hi ? b16 : 0xFFFFu - b16;
-        if (in_window) atomicAdd(&hist[bin], 1u);
+    // bin = pattern (non-negative window) or 0xFFFF - pattern (negative window): one xor with a
+    // uniform mask, done on the packed word for both halves.  A pattern of the other sign comes
+    // out at 0x8000 or above and is counted into one of the kTrashBins words behind the window
+    // (a word of the lane's own, so that the lanes of one instruction do not queue up on one
+    // address): no branch, no lane masking around the LDS atomic.
+    const uint32_t flip = hi ? 0u : 0xFFFFFFFFu;
+    const uint32_t trash = (uint32_t)(kBins + (tid & (kTrashBins - 1)));
+    auto add = [&](uint32_t bin) {                        // bin < 0x10000
+        atomicAdd(&hist[bin < trash ? bin : trash], 1u);
     };
     auto add8 = [&](const u32x4& v) {
-        add(v.x & 0xFFFFu); add(v.x >> 16); add(v.y & 0xFFFFu); add(v.y >> 16);
-        add(v.z & 0xFFFFu); add(v.z >> 16); add(v.w & 0xFFFFu); add(v.w >> 16);
+        const uint32_t x = v.x ^ flip, y = v.y ^ flip, z = v.z ^ flip, w = v.w ^ flip;
+        add(x & 0xFFFFu); add(x >> 16); add(y & 0xFFFFu); add(y >> 16);
+        add(z & 0xFFFFu); add(z >> 16); add(w & 0xFFFFu); add(w >> 16);
     };
     const int64_t nvec = V >> 3;
     const u32x4* rv = reinterpret_cast<const u32x4*>(row);
@@ -91,7 +98,7 @@ __device__ __forceinline__ void build_hist(const uint16_t* __restrict__ row, int
     }
     for (; v < nvec; v += kRThreads) add8(rv[v]);
     const int64_t tail0 = nvec << 3;
-    if (tid < V - tail0) add((uint32_t)row[tail0 + tid]);
+    if (tid < V - tail0) add(((uint32_t)row[tail0 + tid] ^ flip) & 0xFFFFu);
     __syncthreads();
 }
 
@@ -439,7 +446,7 @@ struct RestrictedArgs {
 __global__ __launch_bounds__(kRThreads)
 void sample_restricted_kernel(RestrictedArgs a)
 {
-    __shared__ __align__(16) uint32_t hist[kBins];
+    __shared__ __align__(16) uint32_t hist[kBins + kTrashBins];
     __shared__ Shared sh;
     const int tid = threadIdx.x;
     const int64_t row = blockIdx.x;
