@@ -124,24 +124,6 @@ struct alignas(16) SelShared {
 
 static_assert(offsetof(SelShared, gt_key) % 16 == 0 && offsetof(SelShared, gt_col) % 16 == 0, "read four at a time");
 
-// Largest unsigned value of the wave, returned wave-uniform (DPP butterfly as in wave_best).
-template <int kCtrl, int kRowMask = 0xF>
-__device__ __forceinline__ uint32_t umax_step(uint32_t v)
-{
-    const uint32_t o = (uint32_t)dpp_i<kCtrl, kRowMask>((int)v, (int)v);   // rows masked off see themselves
-    return o > v ? o : v;
-}
-__device__ __forceinline__ uint32_t wave_max_u32(uint32_t v)
-{
-    v = umax_step<kDppXor1>(v);
-    v = umax_step<kDppXor2>(v);
-    v = umax_step<kDppHalfMirror>(v);
-    v = umax_step<kDppMirror>(v);
-    v = umax_step<kDppBcast15, 0xA>(v);
-    v = umax_step<kDppBcast31, 0xC>(v);
-    return (uint32_t)__builtin_amdgcn_readlane((int)v, 63);
-}
-
 // One 8-bit pass of a radix select for the k-th largest: every thread has added its keys
 // that match `prefix` above `shift + 8` to hist; wave 0 finds the digit that holds rank k_rem.
 __device__ __forceinline__ void select_digit(SelShared& sh, int tid)
@@ -495,21 +477,20 @@ void sample_select_kernel(SelArgs a)
         }
         return;
     }
-    // Each wave takes the m-th largest of its lanes' maxima, m = ceil(k / kSWaves), by striking the
-    // largest m - 1 times; the smallest of the waves' results has kSWaves m >= k threads at or above
-    // it.  No atomics, one barrier.  (The exact k-th largest of the thread maxima would be a little
-    // tighter; it costs two to four histogram passes with their barriers.)
+    // Each wave takes the m-th largest of its lanes' maxima, m = ceil(k / kSWaves), bit by bit
+    // from the top with one ballot per bit (the largest value that at least m lanes reach; the
+    // bits below the significant ones stay zero, which only lowers the bound); the smallest of
+    // the waves' results has kSWaves m >= k threads at or above it.  No atomics, one barrier.
+    // (The exact k-th largest of the thread maxima would be a little tighter; it costs two to
+    // four histogram passes with their barriers.)
     const int k_req = a.top_k < kSMaxK ? a.top_k : kSMaxK;
     uint32_t theta;
     {
         const int m_th = (k_req + kSWaves - 1) / kSWaves;
-        uint32_t rest = tmax, wm = 0u;
-        for (int it = 0; it < m_th; ++it) {
-            wm = wave_max_u32(rest);
-            if (it + 1 < m_th) {
-                const unsigned long long holders = __ballot(rest == wm);
-                if (lane == (int)__builtin_ctzll(holders | (1ull << 63))) rest = 0u;
-            }
+        uint32_t wm = 0u;
+        for (int b = 31; b >= 32 - T::kKeyBits; --b) {
+            const uint32_t cand = wm | (1u << b);
+            if (__popcll(__ballot(tmax >= cand)) >= m_th) wm = cand;
         }
         if (lane == 0) sh.tmax_wave[wave] = wm;
         __syncthreads();
