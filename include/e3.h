@@ -173,7 +173,8 @@ int e3_sample_entropy_noalloc(const void* logits, int dtype, int64_t rows, int64
  * One workgroup of 1024 threads per row.  With 1 <= top_k <= 256 the row is read once
  * (vector maxima kept in LDS, the few vectors that can hold one of the k largest read
  * again, exact selection among those); otherwise (bf16 only) a histogram over the 2^16
- * stored patterns in 128 KiB of LDS, one to three sweeps of the row.
+ * stored patterns in 128 KiB of LDS: one counting sweep of the row with 16-bit counters, or,
+ * for a row with 65,536 or more equal columns, one to three sweeps with 32-bit counters.
  */
 int e3_sample_restricted(const void* logits, int dtype, int64_t rows, int64_t V, int64_t row_stride,
                          const float* tau_rows, float tau_scalar, int32_t top_k, float top_p,

@@ -8,22 +8,28 @@
 // over the kept levels followed by a uniform choice among the winning level's columns.
 //
 // bf16 has only 65,536 bit patterns, so a row's whole value distribution fits a
-// count histogram: 32,768 patterns (one sign) x 32-bit counters = 128 KiB of the
-// compute unit's 160 KiB LDS.  One workgroup of 16 waves owns one row:
-//   1. stream the row once, counting the non-negative patterns with LDS atomics
-//      (the columns of a wave instruction scatter over many bins: few conflicts);
-//   2. every thread owns 32 consecutive bins, i.e. 32 equally spaced values of one
-//      binade, whose weights exp((z - z_1)/tau) form a geometric sequence: two
-//      exponentials and 31 products per thread give all level masses in fp64; a
-//      workgroup scan yields the cumulative counts C_j and masses M_j in rank order;
+// count histogram in the compute unit's 160 KiB LDS: all 65,536 patterns with 16-bit
+// counters (128 KiB, two counters per word), or the 32,768 patterns of one sign with
+// 32-bit counters (128 KiB).  One workgroup of 16 waves owns one row:
+//   1. stream the row once, counting with LDS atomics (the columns of a wave
+//      instruction scatter over many words: few conflicts);
+//   2. every thread owns 64 (one window) or 32 (two windows) consecutive bins, i.e.
+//      equally spaced values of one binade, whose weights exp((z - z_1)/tau) form a
+//      geometric sequence: two exponentials and a product per bin give all level masses
+//      in fp64; a workgroup scan yields the cumulative counts C_j and masses M_j in rank
+//      order;
 //   3. the cuts are located by the thread whose bins contain them, the kept levels
 //      race for the draw (n_j w_j / E_j, fp32 like the unrestricted sampler), and a
 //      second sweep over the row (now in L2 / the memory-side cache) finds the pos-th
 //      column of the winning level.
-// Rows whose kept set reaches the negative patterns repeat steps 1-2 on the negative
-// half (same LDS); the rare order of events "top-k cut among the negatives, top-p cut
-// back among the non-negatives" costs a third sweep.  Counts are integers; masses and
-// the cuts are fp64.
+// The one-window form (16-bit counters) serves every setting with that single counting
+// sweep.  A row with a level of 65,536 or more equal columns wraps a counter; it is
+// recognised (the counts no longer add up to the row's width) and redone by the
+// two-window form: non-negative patterns first, and if the kept set reaches the negative
+// patterns steps 1-2 again on the negative half (same LDS); there, top-p without top-k
+// totals the negative half first, and the order of events "top-k cut among the
+// negatives, top-p cut back among the non-negatives" costs a third sweep.  Counts are
+// integers; masses and the cuts are fp64.
 #include "vocab_common.h"
 #include "vocab_pass.h"
 
@@ -50,6 +56,7 @@ struct Shared {
     int best_bits[kRWaves];
     int best_n[kRWaves];
     int wave_hits[kRWaves];
+    int wave_A[kRWaves];
     int first_thread;
     int cut_bin, cut_C;
     double cut_M;
@@ -103,13 +110,15 @@ __device__ __forceinline__ void build_hist(const uint16_t* __restrict__ row, int
 }
 
 // Per-thread view of the scanned window.
-struct View {
-    uint32_t cnt[kOwn];   // counts of my bins; index kOwn-1 is my highest bin
+template <int kOwnT>
+struct ViewT {
+    uint32_t cnt[kOwnT];  // counts of my bins; the last index is my highest bin
     int b0;               // my lowest bin
     double w_top, r_inv;  // weight of my highest bin; factor to the next lower bin
     int Cl, Cx;           // my count; count of all higher levels (carry included)
     double Ml, Mx;        // the same for mass
 };
+using View = ViewT<kOwn>;
 
 // Step 2.  carry_C / carry_M: count and mass of all levels above this window.
 // z1: value of the row's highest level; when `find_z1` it is taken from this window's
@@ -188,7 +197,8 @@ __device__ __forceinline__ bool scan_window(const uint32_t* hist, bool hi, doubl
 }
 
 // First level whose cumulative count reaches k.  Exactly one thread holds it.
-__device__ __forceinline__ void find_count_cut(const View& vw, int k, Shared& sh)
+template <int kOwnT>
+__device__ __forceinline__ void find_count_cut(const ViewT<kOwnT>& vw, int k, Shared& sh)
 {
     if (vw.Cx < k && vw.Cx + vw.Cl >= k) {
         int C = vw.Cx;
@@ -196,7 +206,7 @@ __device__ __forceinline__ void find_count_cut(const View& vw, int k, Shared& sh
         int bin = vw.b0;
         bool done = false;
 #pragma unroll
-        for (int j = kOwn - 1; j >= 0; --j) {
+        for (int j = kOwnT - 1; j >= 0; --j) {
             if (!done) {
                 C += (int)vw.cnt[j];
                 M += (double)vw.cnt[j] * w;
@@ -213,7 +223,8 @@ __device__ __forceinline__ void find_count_cut(const View& vw, int k, Shared& sh
 // per-thread prefixes may disagree in the last bit, so the owner is the first thread
 // whose inclusive prefix reaches T; if rounding lets none of its levels reach T the
 // owner's lowest populated level (or the floor) is taken.
-__device__ __forceinline__ void find_mass_cut(const View& vw, double T, int floor_bin, int floor_C, double floor_M,
+template <int kOwnT>
+__device__ __forceinline__ void find_mass_cut(const ViewT<kOwnT>& vw, double T, int floor_bin, int floor_C, double floor_M,
                               Shared& sh, int tid)
 {
     if (tid == 0) { sh.first_thread = kRThreads; }
@@ -228,7 +239,7 @@ __device__ __forceinline__ void find_mass_cut(const View& vw, double T, int floo
         double M = vw.Mx, w = vw.w_top, Mb = 0.0;
         bool done = false;
 #pragma unroll
-        for (int j = kOwn - 1; j >= 0; --j) {
+        for (int j = kOwnT - 1; j >= 0; --j) {
             if (!done && vw.cnt[j] != 0) {
                 C += (int)vw.cnt[j];
                 M += (double)vw.cnt[j] * w;
@@ -289,6 +300,264 @@ __device__ __forceinline__ RaceBest race_window(const uint32_t* hist, bool hi, i
         if (q > out.q || (from_here && q == out.q && q >= 0.0 && bin_of(sh.best_bits[w]) > bin_of(out.bits))) {
             out.q = q; out.bits = sh.best_bits[w]; out.n = sh.best_n[w];
             from_here = true;
+        }
+    }
+    __syncthreads();
+    return out;
+}
+
+// ---------------------------------------------------------------------------
+// One window.  All 65,536 patterns of a row counted in one sweep, two 16-bit counters per LDS
+// word at the pattern's own index, so that one scan sees the whole row in rank order and no
+// setting needs a second or third sweep.  A counter cannot hold a level of 65,536 columns or
+// more: the counts of a row must add up to its width, a row where they do not (a wrapped
+// counter changes the sum) is handed to the two-window code below, which counts in 32 bits.
+// "Bin" here is the pattern's rank key, ascending in value: 0x8000 + pattern for non-negative
+// patterns, 0xFFFF - pattern for negative ones; thread t owns the 64 bins below 65536 - 64 t,
+// which are 64 consecutive patterns of one sign and one exponent.
+// ---------------------------------------------------------------------------
+constexpr int kBins1 = 65536;
+constexpr int kOwn1 = kBins1 / kRThreads;          // 64
+
+// A thread's share of the one window after the scan.  The counts themselves stay in LDS (64 of
+// them per thread would occupy half the register file across the cut search); the one thread
+// that holds a cut reads its own again.
+struct ScanOne {
+    int b0;               // my lowest bin
+    bool finite;          // my patterns are values (not inf / NaN)
+    double w_top, r_inv;  // weight of my highest bin; factor to the next lower bin
+    int Cl, Cx;           // my count; count of all higher levels
+    double Ml, Mx;        // the same for mass
+};
+
+__device__ __forceinline__ int bits_of_bin1(int bin) { return bin >= 0x8000 ? bin - 0x8000 : 0xFFFF - bin; }
+__device__ __forceinline__ int bin1_of_bits(int bits) { return bits < 0x8000 ? bits + 0x8000 : 0xFFFF - bits; }
+// Word that holds a pattern's counter.  One unused word follows every 32, so that the threads of
+// a wave, each reading the 32 words of its 64 patterns, start in 64 different banks.
+constexpr int kWords1 = kBins1 / 2 + kBins1 / 64;
+__device__ __forceinline__ uint32_t word1(uint32_t bits) { return (bits >> 1) + (bits >> 6); }
+__device__ __forceinline__ uint32_t count1(const uint32_t* hist, int bits)
+{
+    return (hist[word1((uint32_t)bits)] >> ((bits & 1) * 16)) & 0xFFFFu;
+}
+
+__device__ __forceinline__ void build_hist1(const uint16_t* __restrict__ row, int64_t V, uint32_t* hist, int tid)
+{
+    const uint4 zero4 = {0u, 0u, 0u, 0u};
+    for (int i = tid; i < kWords1 / 4; i += kRThreads) reinterpret_cast<uint4*>(hist)[i] = zero4;
+    __syncthreads();
+    auto add2 = [&](uint32_t x) {                       // the two patterns of one word
+        atomicAdd(&hist[word1(x & 0xFFFFu)], (x & 1u) ? 0x10000u : 1u);
+        atomicAdd(&hist[word1(x >> 16)], (x & 0x10000u) ? 0x10000u : 1u);
+    };
+    auto add8 = [&](const u32x4& v) { add2(v.x); add2(v.y); add2(v.z); add2(v.w); };
+    const int64_t nvec = V >> 3;
+    const u32x4* rv = reinterpret_cast<const u32x4*>(row);
+    int64_t v = tid;
+    for (; v + 3 * kRThreads < nvec; v += 4 * kRThreads) {
+        const u32x4 a = rv[v], b = rv[v + kRThreads], c = rv[v + 2 * kRThreads], d = rv[v + 3 * kRThreads];
+        add8(a); add8(b); add8(c); add8(d);
+    }
+    for (; v < nvec; v += kRThreads) add8(rv[v]);
+    const int64_t tail0 = nvec << 3;
+    if (tid < V - tail0) {
+        const uint32_t pat = row[tail0 + tid];
+        atomicAdd(&hist[word1(pat)], (pat & 1u) ? 0x10000u : 1u);
+    }
+    __syncthreads();
+}
+
+// Scan of the one window.  Returns 0 if a counter has wrapped (the caller falls back), 1 if
+// the row has no finite value, 2 otherwise, with z1 = the row's highest level, the window's
+// count and mass in Cw / Mw and the thread's view filled in.
+__device__ __forceinline__ int scan_one_window(const uint32_t* hist, int64_t V, double inv_tau, double& z1,
+                                               ScanOne& vw, int& Cw, double& Mw, Shared& sh, int tid)
+{
+    const int lane = tid & 63, wave = tid >> 6;
+    vw.b0 = kBins1 - kOwn1 * (tid + 1);                // thread 0 owns the highest bins
+    const bool nonneg = vw.b0 >= 0x8000;
+    const int p_low = nonneg ? vw.b0 - 0x8000 : 0xFFFF - (vw.b0 + kOwn1 - 1);    // my lowest pattern, a multiple of 64
+    const int exp_field = (p_low >> 7) & 0xFF;         // the same for all my patterns
+    const bool finite = exp_field != 0xFF;             // inf / NaN patterns are not levels
+    vw.finite = finite;
+    int all = 0, Cl = 0, my_top = -1;
+    uint32_t cnt[kOwn1];                               // in bin order; dead once my mass is summed
+    // ascending bin = ascending pattern for non-negative values, descending for negative ones:
+    // the negative half reads its words, and the two counters of a word, in reverse
+#pragma unroll
+    for (int i = 0; i < kOwn1 / 2; ++i) {
+        const uint32_t word = hist[word1((uint32_t)p_low) + (nonneg ? i : kOwn1 / 2 - 1 - i)];
+        const uint32_t lo = word & 0xFFFFu, hi = word >> 16;
+        const uint32_t n0 = nonneg ? lo : hi, n1 = nonneg ? hi : lo;
+        all += (int)(n0 + n1);
+        cnt[2 * i] = finite ? n0 : 0u;
+        cnt[2 * i + 1] = finite ? n1 : 0u;
+        Cl += (int)(cnt[2 * i] + cnt[2 * i + 1]);
+        if (cnt[2 * i] != 0) my_top = vw.b0 + 2 * i;
+        if (cnt[2 * i + 1] != 0) my_top = vw.b0 + 2 * i + 1;
+    }
+    vw.Cl = Cl;
+#pragma unroll
+    for (int d = 32; d > 0; d >>= 1) all += __shfl_xor(all, d, 64);
+    const float t = wave_max((float)my_top);           // bins are below 2^16: exact in fp32
+    if (lane == 0) { sh.wave_top[wave] = t; sh.wave_A[wave] = all; }
+    __syncthreads();
+    float top = -1.0f;
+    long long total = 0;
+    for (int w = 0; w < kRWaves; ++w) { top = fmaxf(top, sh.wave_top[w]); total += sh.wave_A[w]; }
+    __syncthreads();
+    if (total != (long long)V) return 0;
+    if (top < 0.0f) { Cw = 0; Mw = 0.0; return 1; }
+    z1 = bf16_value(bits_of_bin1((int)top));
+    // my 64 values are equally spaced (half a binade, or subnormals): geometric weights
+    double Ml = 0.0;
+    vw.w_top = 0.0; vw.r_inv = 0.0;
+    if (Cl > 0) {
+        const double z_top = bf16_value(bits_of_bin1(vw.b0 + kOwn1 - 1));
+        const double step = ldexp(1.0, (exp_field ? exp_field : 1) - 134);
+        vw.w_top = exp((z_top - z1) * inv_tau);
+        vw.r_inv = exp(-step * inv_tau);
+        double w = vw.w_top;
+#pragma unroll
+        for (int j = kOwn1 - 1; j >= 0; --j) {
+            Ml += (double)cnt[j] * w;
+            w *= vw.r_inv;
+        }
+    }
+    vw.Ml = Ml;
+    // exclusive scan in thread order (= rank order)
+    int Ci = Cl;
+    double Mi = Ml;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        const int c = __shfl_up(Ci, d, 64);
+        const double m = __shfl_up(Mi, d, 64);
+        if (lane >= d) { Ci += c; Mi += m; }
+    }
+    if (lane == 63) { sh.wave_C[wave] = Ci; sh.wave_M[wave] = Mi; }
+    __syncthreads();
+    int Cb = 0, Ct = 0;
+    double Mb = 0.0, Mt = 0.0;
+    for (int w = 0; w < kRWaves; ++w) {
+        if (w < wave) { Cb += sh.wave_C[w]; Mb += sh.wave_M[w]; }
+        Ct += sh.wave_C[w]; Mt += sh.wave_M[w];
+    }
+    __syncthreads();
+    vw.Cx = Cb + Ci - Cl;
+    vw.Mx = Mb + (Mi - Ml);
+    Cw = Ct; Mw = Mt;
+    return 2;
+}
+
+// The two cut searches of the one window: as find_count_cut / find_mass_cut, with the owner
+// thread reading its counts from LDS again.
+// The owner's 64 counts in bin order, read in one go (its 32 words are consecutive).
+__device__ __forceinline__ void own_counts1(const uint32_t* hist, const ScanOne& vw, uint32_t cnt[kOwn1])
+{
+    const bool nonneg = vw.b0 >= 0x8000;
+    const int p_low = nonneg ? vw.b0 - 0x8000 : 0xFFFF - (vw.b0 + kOwn1 - 1);
+#pragma unroll
+    for (int i = 0; i < kOwn1 / 2; ++i) {
+        const uint32_t word = hist[word1((uint32_t)p_low) + (nonneg ? i : kOwn1 / 2 - 1 - i)];
+        const uint32_t lo = word & 0xFFFFu, hi = word >> 16;
+        cnt[2 * i] = vw.finite ? (nonneg ? lo : hi) : 0u;
+        cnt[2 * i + 1] = vw.finite ? (nonneg ? hi : lo) : 0u;
+    }
+}
+
+__device__ __forceinline__ void find_count_cut1(const uint32_t* hist, const ScanOne& vw, int k, Shared& sh)
+{
+    if (vw.Cx < k && vw.Cx + vw.Cl >= k) {
+        int C = vw.Cx;
+        double M = vw.Mx, w = vw.w_top;
+        int bin = vw.b0;
+        uint32_t cnt[kOwn1];
+        own_counts1(hist, vw, cnt);
+        bool done = false;
+#pragma unroll
+        for (int j = kOwn1 - 1; j >= 0; --j) {
+            if (!done) {
+                C += (int)cnt[j];
+                M += (double)cnt[j] * w;
+                if (C >= k) { bin = vw.b0 + j; done = true; }
+            }
+            w *= vw.r_inv;
+        }
+        sh.cut_bin = bin; sh.cut_C = C; sh.cut_M = M;
+    }
+    __syncthreads();
+}
+
+__device__ __forceinline__ void find_mass_cut1(const uint32_t* hist, const ScanOne& vw, double T, int floor_bin,
+                                               int floor_C, double floor_M, Shared& sh, int tid)
+{
+    if (tid == 0) { sh.first_thread = kRThreads; }
+    __syncthreads();
+    if (vw.Cl > 0 && vw.Mx + vw.Ml >= T) atomicMin(&sh.first_thread, tid);
+    __syncthreads();
+    const int owner = sh.first_thread;
+    if (owner == kRThreads) {                        // nobody reaches T: keep down to the floor
+        if (tid == 0) { sh.cut_bin = floor_bin; sh.cut_C = floor_C; sh.cut_M = floor_M; }
+    } else if (tid == owner) {
+        int C = vw.Cx, bin = -1, Cb = 0;
+        double M = vw.Mx, w = vw.w_top, Mb = 0.0;
+        uint32_t cnt[kOwn1];
+        own_counts1(hist, vw, cnt);
+        bool done = false;
+#pragma unroll
+        for (int j = kOwn1 - 1; j >= 0; --j) {
+            if (!done && cnt[j] != 0) {
+                C += (int)cnt[j];
+                M += (double)cnt[j] * w;
+                bin = vw.b0 + j; Cb = C; Mb = M;      // lowest populated level so far
+                if (M >= T) done = true;
+            }
+            w *= vw.r_inv;
+        }
+        if (bin < floor_bin) { bin = floor_bin; Cb = floor_C; Mb = floor_M; }
+        sh.cut_bin = bin; sh.cut_C = Cb; sh.cut_M = Mb;
+    }
+    __syncthreads();
+}
+
+// Race of the levels in bins [cut_bin, 65536) of the one window; same scores, same tie
+// rule (the higher value) as race_window.
+__device__ __forceinline__ RaceBest race_one_window(const uint32_t* hist, int cut_bin, double z1, float c,
+                                                    uint64_t seed, uint64_t grow, Shared& sh, int tid)
+{
+    const int lane = tid & 63, wave = tid >> 6;
+    const float z1f = (float)z1;                      // a bf16 value: exact
+    RaceBest mine{-1.0, 0, 0};
+    for (int bin = kBins1 - 1 - tid; bin >= cut_bin; bin -= kRThreads) {
+        const int bits = bits_of_bin1(bin);
+        const uint32_t n = count1(hist, bits);
+        if (n == 0 || ((bits >> 7) & 0xFF) == 0xFF) continue;
+        uint32_t w4[4];
+        philox4x32_10((uint32_t)bits >> 2, (uint32_t)grow, (uint32_t)(grow >> 32), 3u,
+                      (uint32_t)seed, (uint32_t)(seed >> 32), w4);
+        const int sel = bits & 3;
+        const uint32_t word = sel == 0 ? w4[0] : sel == 1 ? w4[1] : sel == 2 ? w4[2] : w4[3];
+        const float z = __uint_as_float((uint32_t)bits << 16);
+        const float q = (float)n * __builtin_amdgcn_exp2f((z - z1f) * c) * inv_exp_variate(word);
+        // a thread meets its bins in falling value order: `>` keeps the higher level on ties
+        if ((double)q > mine.q) { mine.q = (double)q; mine.bits = bits; mine.n = (int)n; }
+    }
+#pragma unroll
+    for (int d = 32; d > 0; d >>= 1) {
+        const double oq = __shfl_xor(mine.q, d, 64);
+        const int ob = __shfl_xor(mine.bits, d, 64);
+        const int on = __shfl_xor(mine.n, d, 64);
+        if (oq > mine.q || (oq == mine.q && oq >= 0.0 && bin1_of_bits(ob) > bin1_of_bits(mine.bits))) {
+            mine.q = oq; mine.bits = ob; mine.n = on;
+        }
+    }
+    if (lane == 0) { sh.best_q[wave] = mine.q; sh.best_bits[wave] = mine.bits; sh.best_n[wave] = mine.n; }
+    __syncthreads();
+    RaceBest out{-1.0, 0, 0};
+    for (int w = 0; w < kRWaves; ++w) {
+        const double q = sh.best_q[w];
+        if (q > out.q || (q == out.q && q >= 0.0 && bin1_of_bits(sh.best_bits[w]) > bin1_of_bits(out.bits))) {
+            out.q = q; out.bits = sh.best_bits[w]; out.n = sh.best_n[w];
         }
     }
     __syncthreads();
@@ -446,7 +715,7 @@ struct RestrictedArgs {
 __global__ __launch_bounds__(kRThreads)
 void sample_restricted_kernel(RestrictedArgs a)
 {
-    __shared__ __align__(16) uint32_t hist[kBins + kTrashBins];
+    __shared__ __align__(16) uint32_t hist[kWords1 > kBins + kTrashBins ? kWords1 : kBins + kTrashBins];
     __shared__ Shared sh;
     const int tid = threadIdx.x;
     const int64_t row = blockIdx.x;
@@ -461,13 +730,44 @@ void sample_restricted_kernel(RestrictedArgs a)
     const double p = (double)a.top_p;
     const int k = a.top_k;
 
-    View vw;
     double z1 = 0.0;
-    int C_hi = 0, C_lo = 0;
-    double M_hi = 0.0, M_lo = 0.0;
     RaceBest best{-1.0, 0, 0};
     int kept_C = 0;
     double kept_M = 0.0;
+
+    // One sweep, one scan, whatever the setting; rows with a level too long for a 16-bit
+    // counter take the two-window code after it.
+    bool done = false;
+    {
+        ScanOne v1;
+        int C_all = 0;
+        double M_all = 0.0;
+        build_hist1(rowp, V, hist, tid);
+        const int state = scan_one_window(hist, V, inv_tau, z1, v1, C_all, M_all, sh, tid);
+        if (state != 0) {
+            done = true;
+            if (state == 2) {
+                int cb = 0;
+                kept_C = C_all; kept_M = M_all;
+                if (k_on && C_all >= k) {
+                    find_count_cut1(hist, v1, k, sh);
+                    cb = sh.cut_bin; kept_C = sh.cut_C; kept_M = sh.cut_M;
+                    __syncthreads();
+                }
+                if (p_on) {
+                    find_mass_cut1(hist, v1, p * kept_M, cb, kept_C, kept_M, sh, tid);
+                    cb = sh.cut_bin; kept_C = sh.cut_C; kept_M = sh.cut_M;
+                    __syncthreads();
+                }
+                best = race_one_window(hist, cb, z1, c, a.seed, grow, sh, tid);
+            }
+        }
+    }
+
+    View vw;
+    int C_hi = 0, C_lo = 0;
+    double M_hi = 0.0, M_lo = 0.0;
+    if (!done) {
 
     // Without top-k the nucleus target is a fraction of the whole row's mass, which
     // includes the negative patterns: total them first, relative to the value 0.
@@ -560,6 +860,8 @@ void sample_restricted_kernel(RestrictedArgs a)
             }
         }
     }
+
+    }   // two-window code
 
     // the column inside the winning level
     uint32_t w4[4];

@@ -89,6 +89,26 @@ def test_widest_accepted_row():
 
 
 @pytest.mark.gpu
+def test_levels_longer_than_a_16_bit_counter():
+    # the one-sweep form counts in 16 bits; a level of 65,536 columns or more wraps its counter
+    # (into its neighbour when it sits in the low half of a word, into nothing in the high half)
+    # and the row must be recognised and recounted in 32 bits.  65,535 still fits.
+    V = 200_000
+    g = torch.Generator(device=DEV).manual_seed(45)
+    even, odd = 0.5, 0.50390625                        # bf16 patterns 0x3F00 and 0x3F01: one LDS word
+    base = (torch.randn((6, V), generator=g, device=DEV) * 0.05 - 2.0)
+    runs = [(65_536, even, 0, odd), (65_536, odd, 0, even), (65_535, even, 65_535, odd),
+            (70_000, odd, 3, even), (131_072, even, 1, odd), (65_537, odd, 65_536, even)]
+    for r, (n_a, v_a, n_b, v_b) in enumerate(runs):
+        perm = torch.randperm(V, generator=g, device=DEV)
+        base[r, perm[:n_a]] = v_a
+        base[r, perm[n_a:n_a + n_b]] = v_b
+    lg = base.to(torch.bfloat16)
+    for k, p in [(0, 0.9), (1000, 1.0), (0, 0.2), (100_000, 0.999), (300, 0.5)]:
+        check(lg, None, 1.0, k, p, 21, 5, f"long levels k={k} p={p}")
+
+
+@pytest.mark.gpu
 def test_repeated_values_and_signed_zeros():
     # few distinct values: every level holds many columns, cuts fall inside repeated values
     g = torch.Generator(device=DEV).manual_seed(8)
