@@ -112,9 +112,11 @@ def main() -> int:
     ap.add_argument("--no-other-configs", action="store_true",
                     help="skip the kernel timings on configs 3 (dynamic budgets), 4 (training pass) and "
                          "5 (large decode batch) that the default run reports in `other_configs`")
-    ap.add_argument("--restricted", action="store_true",
-                    help="also time e3_sample_restricted (top-k / top-p settings, bf16 and fp32 rows) on the same batches and "
-                         "report it in a `restricted_sampling` object; not part of the step")
+    ap.add_argument("--no-restricted", action="store_true",
+                    help="skip the timings of e3_sample_restricted (top-k / top-p settings, bf16 and fp32 rows, on "
+                         "the same rotating batches) that the default run reports in `restricted_sampling`; "
+                         "they are not part of the step")
+    ap.add_argument("--restricted", action="store_true", help="accepted for older command lines: the default now")
     ap.add_argument("--sizes", action="store_true",
                     help="also time the two vocabulary-pass kernels and the read probe on other batch "
                          "sizes and on fp32 logits (back-to-back launches, dispatch events)")
@@ -309,14 +311,14 @@ def main() -> int:
     out["roofline"]["frac_of_read_ceiling"] = achieved / out["read_ceiling"]["GBps"]
     out["roofline"]["limiter"] = limiter(kern_avg_ms, out["read_ceiling"]["avg_ms"])
     out["roofline"]["limiter_rule"] = LIMITER_RULE
+    if not args.no_restricted:                       # before the buffers are released: it rotates over them
+        out["restricted_sampling"] = restricted_leg(e3, batches, stream)
     if not args.no_other_configs:
         keep = batches[0]
         del batches
         torch.cuda.empty_cache()
         batches = [keep]
         out["other_configs"] = other_configs_leg(e3, wl, dev, dev_events)
-    if args.restricted:
-        out["restricted_sampling"] = restricted_leg(e3, batches, stream)
     if args.sizes:
         del batches[1:]
         torch.cuda.empty_cache()
