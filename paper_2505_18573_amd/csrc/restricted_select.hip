@@ -490,7 +490,7 @@ void sample_select_kernel(SelArgs a)
         uint32_t wm = 0u;
         for (int b = 31; b >= 32 - T::kKeyBits; --b) {
             const uint32_t cand = wm | (1u << b);
-            if (__popcll(__ballot(tmax >= cand)) >= m_th) wm = cand;
+            if ((int)__popcll(__ballot(tmax >= cand)) >= m_th) wm = cand;
         }
         if (lane == 0) sh.tmax_wave[wave] = wm;
         __syncthreads();
